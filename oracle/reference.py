@@ -1,0 +1,153 @@
+"""ctypes front end of the CPU oracle (oracle/brgemm_oracle.c).
+
+TEST INFRASTRUCTURE: only the tests, the smoke check and the benchmark's
+CPU-baseline leg may import this module.  It imports nothing from the GPU
+package and the GPU package imports nothing from here.
+
+The arithmetic lives in the C file; this module only marshals numpy arrays.
+Element types: numpy float32 = fp32, numpy uint16 = bf16 bit patterns.
+
+Defines (Algorithm 1's input/output statement; Section 2.1 for scattered
+tiles; Section 5(d) for GEMM as the batch-1 case):
+
+    ref = beta * C0 + sum_i A_i x B_i      (fp64, every input widened exactly)
+"""
+import ctypes
+import os
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "liboracle_brgemm.so")
+_lib = None
+
+F32, BF16 = 0, 1
+
+
+def _load():
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(_LIB_PATH):
+        from . import build as _b  # building the checker is not using it
+        _b.build(force=True)
+    lib = ctypes.CDLL(_LIB_PATH)
+    i64, vp, cint = ctypes.c_int64, ctypes.c_void_p, ctypes.c_int
+    lib.oracle_brgemm.restype = cint
+    lib.oracle_brgemm.argtypes = [cint, cint, cint, i64, i64, i64, i64,
+                                  vp, vp, i64, vp, vp, i64,
+                                  ctypes.c_float, vp, cint, i64,
+                                  vp, cint, vp, i64, vp]
+    lib.oracle_round_to_out.restype = None
+    lib.oracle_round_to_out.argtypes = [vp, i64, cint, vp]
+    lib.oracle_f64_to_bf16.restype = ctypes.c_uint16
+    lib.oracle_f64_to_bf16.argtypes = [ctypes.c_double]
+    lib.oracle_bf16_to_f64.restype = ctypes.c_double
+    lib.oracle_bf16_to_f64.argtypes = [ctypes.c_uint16]
+    lib.oracle_num_threads.restype = cint
+    lib.oracle_num_threads.argtypes = []
+    _lib = lib
+    return lib
+
+
+def _dtype_code(a):
+    if a.dtype == np.float32:
+        return F32
+    if a.dtype == np.uint16:
+        return BF16
+    raise TypeError(f"oracle takes float32 or uint16 (bf16 bits), got {a.dtype}")
+
+
+def _ptr(a):
+    return ctypes.c_void_p(a.ctypes.data) if a is not None else ctypes.c_void_p(0)
+
+
+def num_threads():
+    return int(_load().oracle_num_threads())
+
+
+def brgemm_ref(A_base, A_off, lda, B_base, B_off, ldb, M, N, K, *,
+               transA=0, transB=0, beta=0.0, C0=None, ldc0=None,
+               bias=None, relu=False, rows=None):
+    """fp64 reference of C = beta*C0 + sum_i A_i x B_i (optionally + bias, ReLU).
+
+    A_base/B_base: flat (or any-shape, C-contiguous) arrays; tile i starts at
+    element A_off[i] / B_off[i].  rows: optional list of row indices of C to
+    compute (result is len(rows) x N); default all M rows.
+    """
+    lib = _load()
+    A_base = np.ascontiguousarray(A_base)
+    B_base = np.ascontiguousarray(B_base)
+    dt = _dtype_code(A_base)
+    if _dtype_code(B_base) != dt:
+        raise TypeError("A and B must have the same element type")
+    A_off = np.ascontiguousarray(np.asarray(A_off, dtype=np.int64))
+    B_off = np.ascontiguousarray(np.asarray(B_off, dtype=np.int64))
+    batch = int(A_off.shape[0])
+    if B_off.shape[0] != batch:
+        raise ValueError("A_off and B_off differ in length")
+    # Host-side bounds check so a wrong offset fails here, not in C.
+    if batch and M and N and K:
+        a_span = ((K - 1) * lda + M) if transA else ((M - 1) * lda + K)
+        b_span = ((N - 1) * ldb + K) if transB else ((K - 1) * ldb + N)
+        if A_off.min() < 0 or A_off.max() + a_span > A_base.size:
+            raise ValueError("A tile out of bounds")
+        if B_off.min() < 0 or B_off.max() + b_span > B_base.size:
+            raise ValueError("B tile out of bounds")
+    c0_dt = F32
+    if beta != 0.0:
+        if C0 is None:
+            raise ValueError("beta != 0 needs C0")
+        C0 = np.ascontiguousarray(C0)
+        c0_dt = _dtype_code(C0)
+        if ldc0 is None:
+            ldc0 = N
+        if M and N and (M - 1) * ldc0 + N > C0.size:
+            raise ValueError("C0 out of bounds")
+    else:
+        C0, ldc0 = None, 0
+    if bias is not None:
+        bias = np.ascontiguousarray(bias, dtype=np.float32)
+        if bias.size != N:
+            raise ValueError("bias must have N entries")
+    rows_arr = None
+    R = M
+    if rows is not None:
+        rows_arr = np.ascontiguousarray(np.asarray(rows, dtype=np.int64))
+        R = int(rows_arr.shape[0])
+    ref = np.empty((R, N), dtype=np.float64)
+    rc = lib.oracle_brgemm(dt, int(transA), int(transB), M, N, K, batch,
+                           _ptr(A_base), _ptr(A_off), lda,
+                           _ptr(B_base), _ptr(B_off), ldb,
+                           ctypes.c_float(beta), _ptr(C0), c0_dt, int(ldc0),
+                           _ptr(bias), int(bool(relu)),
+                           _ptr(rows_arr), R, _ptr(ref))
+    if rc != 0:
+        raise ValueError("oracle_brgemm rejected its arguments")
+    return ref
+
+
+def gemm_ref(A, lda, B, ldb, M, N, K, **kw):
+    """fp64 reference of C = beta*C0 + A x B: the batch == 1 case (Section 5(d))."""
+    return brgemm_ref(A, [0], lda, B, [0], ldb, M, N, K, **kw)
+
+
+def round_to_out(ref, out_dtype):
+    """Round an fp64 result once to the library's output type (F32 or BF16 bits)."""
+    lib = _load()
+    ref = np.ascontiguousarray(ref, dtype=np.float64)
+    out = np.empty(ref.shape, dtype=np.uint16 if out_dtype == BF16 else np.float32)
+    lib.oracle_round_to_out(_ptr(ref), ref.size, out_dtype, _ptr(out))
+    return out
+
+
+def f64_to_bf16(x):
+    return int(_load().oracle_f64_to_bf16(float(x)))
+
+
+def bf16_to_f64(bits):
+    """Exact widening of bf16 bit patterns (scalar or array) to fp64."""
+    if np.isscalar(bits):
+        return float(_load().oracle_bf16_to_f64(int(bits)))
+    b = np.asarray(bits, dtype=np.uint16)
+    return (b.astype(np.uint32) << 16).view(np.float32).astype(np.float64)
