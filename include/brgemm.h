@@ -1,0 +1,161 @@
+/*
+ * brgemm.h - C ABI of the MI355X (gfx950) GEMM / batch-reduce GEMM library.
+ *
+ * The operation is the one stated as input/output of Algorithm 1
+ * ("BRGEMM - nanokernels()") of the paper:
+ *
+ *        C  =  beta * C  +  sum_{i=0}^{batch-1}  A_i (M x K)  x  B_i (K x N)
+ *
+ * with plain matrix multiplication as its batch == 1 case (Section 5(d)).
+ * There is no alpha.  beta is an fp32 scalar; beta == 0 means C is written
+ * without ever being read, so NaN or Inf in the old C do not propagate.
+ *
+ * Conventions shared by every entry point
+ * ---------------------------------------
+ *  - All matrices are row-major.  ldX is the number of ELEMENTS between the
+ *    starts of two consecutive stored rows (>= the stored row length).
+ *  - transA == 0: A_i is stored as M x K;  transA == 1: stored as K x M.
+ *    transB == 0: B_i is stored as K x N;  transB == 1: stored as N x K
+ *    (the usual "NT" weight layout).  Section 4.3 ("Flat Layout") is the
+ *    passage that says which operand needs re-laying-out for which storage
+ *    order; here both orders of both operands are accepted.
+ *  - Every pointer is a DEVICE pointer (hipMalloc / torch CUDA tensor), unless
+ *    the argument says "host".  The caller owns every buffer.  The library never
+ *    allocates, frees or synchronises: work is enqueued on `stream` (a
+ *    hipStream_t passed as void*, NULL = the default stream) and the call
+ *    returns at once.  C must not overlap A, B or the workspace.  A_i / B_i
+ *    tiles may overlap one another (they are only read).
+ *  - Any M, N, K, batch >= 0 and any alignment is accepted.  M == 0 or N == 0
+ *    is a no-op.  K == 0 or batch == 0 gives C = beta * C.  The tuned kernels are
+ *    taken when bases/offsets are 16-byte aligned and the leading dimensions
+ *    are multiples of 8 (bf16) or 4 (fp32) elements; anything else runs on a
+ *    slower general kernel with the same results.
+ *  - `workspace` may be NULL (workspace_bytes == 0): then no variant that
+ *    splits the reduction over several workgroups is chosen.  When given it
+ *    must be 256-byte aligned; gemm_workspace_bytes() returns a size that is
+ *    always enough.  Its contents before and after a call are unspecified.
+ *    Two calls that share a workspace must be ordered on one stream.
+ *  - Return value: 0 on success, a negative BRGEMM_* code otherwise.  Nothing
+ *    is launched when an argument is rejected.  No exception or abort crosses
+ *    this boundary.
+ *  - Thread safety: calls may be made concurrently from several host threads.
+ *
+ * Arithmetic: bf16 factors are widened exactly, products and sums are fp32
+ * (the appendix listings of the paper: widen, multiply, add into an f32
+ * accumulator); the accumulator tile stays in registers across the whole K and
+ * batch loops (Section 2.1, advantage (1)); beta*C and the optional bias are
+ * added in fp32; a bf16 C is widened on read and narrowed once, with
+ * round-to-nearest-even, on the final store (Section 4.3, VNNI-packed
+ * paragraph).  The order of the fp32 summation is unspecified.
+ */
+#ifndef BRGEMM_H
+#define BRGEMM_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum {
+    BRGEMM_OK = 0,
+    BRGEMM_INVALID_ARG = -1,         /* negative size, ld too small, bad flag, NULL operand   */
+    BRGEMM_UNSUPPORTED = -2,         /* reserved; no currently accepted input returns it      */
+    BRGEMM_WORKSPACE_TOO_SMALL = -3, /* a forced split variant needs more workspace           */
+    BRGEMM_HIP_ERROR = -4,           /* launch failed; see gemm_last_hip_error()              */
+    BRGEMM_MISALIGNED_WORKSPACE = -5
+};
+
+/* Element types, for gemm_workspace_bytes(). */
+enum { BRGEMM_DTYPE_F32 = 0, BRGEMM_DTYPE_BF16 = 1 };
+
+/* Epilogue flags (Section 6: the measured "MLP kernel" fuses bias and ReLU
+ * before the store of the accumulator). */
+enum { BRGEMM_EPI_NONE = 0, BRGEMM_EPI_BIAS = 1, BRGEMM_EPI_RELU = 2 };
+
+/*
+ * fp32 GEMM:  C[M,N] = beta*C + A[M,K] x B[K,N]   (Algorithm 1, f32 branch).
+ * A, B, C: device, fp32.  lda/ldb/ldc in elements.
+ */
+int gemm_f32(int transA, int transB, int64_t M, int64_t N, int64_t K,
+             const float *A, int64_t lda, const float *B, int64_t ldb,
+             float beta, float *C, int64_t ldc,
+             void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * bf16 GEMM with fp32 accumulation (Algorithm 1, bf16 branches; both storage
+ * orders of B are the paper's "Flat" layout, no pre-packing is required).
+ * A, B: device, bf16 bit patterns.  C: device; fp32 if c_is_f32 != 0, else
+ * bf16 (widened on read when beta != 0, rounded to nearest-even on store).
+ */
+int gemm_bf16(int transA, int transB, int64_t M, int64_t N, int64_t K,
+              const uint16_t *A, int64_t lda, const uint16_t *B, int64_t ldb,
+              float beta, void *C, int64_t ldc, int c_is_f32,
+              void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * bf16 batch-reduce GEMM into an fp32 C (Algorithm 1 as a whole; Section 2.1:
+ * the source tiles need not be contiguous).  Tile i of A starts at element
+ * A_base + A_off[i], tile i of B at B_base + B_off[i]; M, N, K, lda, ldb and
+ * the transpose flags are common to all tiles.  A_off and B_off are DEVICE
+ * arrays of `batch` int64 element offsets (not bytes); they are read by the
+ * kernel, so they must stay valid until the work has run.
+ */
+int brgemm_bf16(int transA, int transB, int64_t M, int64_t N, int64_t K, int64_t batch,
+                const uint16_t *A_base, const int64_t *A_off, int64_t lda,
+                const uint16_t *B_base, const int64_t *B_off, int64_t ldb,
+                float beta, float *C, int64_t ldc,
+                void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * The same three operations with the fused epilogue of Section 6:
+ *     C = act( beta*C + sum_i A_i x B_i + bias[n] )
+ * `epilogue` is a bit set of BRGEMM_EPI_BIAS (bias: device, N fp32 values, may
+ * be NULL when the flag is clear) and BRGEMM_EPI_RELU (negative results become
+ * +0; NaN stays NaN).  in_dtype selects fp32 or bf16 operands; for fp32
+ * operands C is fp32.  batch == 1 with NULL offset arrays is plain GEMM.
+ */
+int brgemm_fused(int in_dtype, int transA, int transB,
+                 int64_t M, int64_t N, int64_t K, int64_t batch,
+                 const void *A_base, const int64_t *A_off, int64_t lda,
+                 const void *B_base, const int64_t *B_off, int64_t ldb,
+                 float beta, void *C, int64_t ldc, int c_is_f32,
+                 const float *bias, int epilogue,
+                 void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * Upper bound, in bytes, of the workspace any variant may use for a problem of
+ * this element type and size (batch = 1 for the GEMM calls).  Never fails;
+ * returns 0 for empty problems.
+ */
+size_t gemm_workspace_bytes(int dtype, int64_t M, int64_t N, int64_t K, int64_t batch);
+
+/* Static, NUL-terminated description of a return code. */
+const char *gemm_strerror(int code);
+
+/* The hipError_t (as int) behind the calling thread's most recent
+ * BRGEMM_HIP_ERROR, 0 if none. */
+int gemm_last_hip_error(void);
+
+/*
+ * Tuning override, for benchmarks and tests: force the kernel variant and the
+ * reduction split of subsequent calls from this thread.  variant < 0 and
+ * split <= 0 restore automatic selection.  A forced variant whose alignment
+ * or workspace requirements are not met makes the call fail with
+ * BRGEMM_INVALID_ARG / BRGEMM_WORKSPACE_TOO_SMALL rather than silently falling back.
+ * Returns BRGEMM_OK, or BRGEMM_INVALID_ARG for an unknown variant.
+ */
+int gemm_force_variant(int variant, int split);
+
+/* Name of variant number v ("" past the end): lets a harness enumerate them. */
+const char *gemm_variant_name(int v);
+
+/* The variant and split the calling thread's most recent successful call used. */
+int gemm_last_variant(void);
+int gemm_last_split(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* BRGEMM_H */

@@ -1,0 +1,182 @@
+"""Thin ctypes binding of libbrgemm_gfx950.so (include/brgemm.h).
+
+Argument marshalling only: every step of the computation runs in the HIP
+kernels behind the C ABI.  torch is used for device memory and streams.  The
+library is loaded on first use; if it has not been built the call raises -
+there is no CPU fallback.
+
+Functions mirror the C entry points by name: gemm_f32, gemm_bf16, brgemm_bf16,
+brgemm_fused, gemm_workspace_bytes, gemm_strerror, gemm_force_variant, ...
+Tensor arguments are torch CUDA tensors (bf16 data may be torch.bfloat16,
+torch.int16 or torch.uint16 - only the pointer is used); sizes and leading
+dimensions are explicit, exactly as in the C signatures.
+"""
+import ctypes
+import os
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libbrgemm_gfx950.so")
+
+OK = 0
+INVALID_ARG = -1
+UNSUPPORTED = -2
+WORKSPACE_TOO_SMALL = -3
+HIP_ERROR = -4
+MISALIGNED_WORKSPACE = -5
+DTYPE_F32, DTYPE_BF16 = 0, 1
+EPI_NONE, EPI_BIAS, EPI_RELU = 0, 1, 2
+
+EXPORTS = ["gemm_f32", "gemm_bf16", "brgemm_bf16", "brgemm_fused", "gemm_workspace_bytes",
+           "gemm_strerror", "gemm_last_hip_error", "gemm_force_variant", "gemm_variant_name",
+           "gemm_last_variant", "gemm_last_split"]
+
+_lib = None
+
+
+class BrgemmError(RuntimeError):
+    def __init__(self, code, where):
+        self.code = code
+        super().__init__(f"{where} failed: {strerror(code)} (code {code})")
+
+
+def load():
+    """Load the shared library (once).  Raises if it is missing."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise RuntimeError(
+            f"{LIB_PATH} is missing: build it with `python -m paper_2511_13764_amd.build` "
+            "(there is no CPU fallback)")
+    lib = ctypes.CDLL(LIB_PATH)
+    i64, vp, ci, cf, sz = ctypes.c_int64, ctypes.c_void_p, ctypes.c_int, ctypes.c_float, ctypes.c_size_t
+    lib.gemm_f32.restype = ci
+    lib.gemm_f32.argtypes = [ci, ci, i64, i64, i64, vp, i64, vp, i64, cf, vp, i64, vp, sz, vp]
+    lib.gemm_bf16.restype = ci
+    lib.gemm_bf16.argtypes = [ci, ci, i64, i64, i64, vp, i64, vp, i64, cf, vp, i64, ci, vp, sz, vp]
+    lib.brgemm_bf16.restype = ci
+    lib.brgemm_bf16.argtypes = [ci, ci, i64, i64, i64, i64, vp, vp, i64, vp, vp, i64, cf, vp, i64, vp, sz, vp]
+    lib.brgemm_fused.restype = ci
+    lib.brgemm_fused.argtypes = [ci, ci, ci, i64, i64, i64, i64, vp, vp, i64, vp, vp, i64, cf, vp, i64, ci,
+                                 vp, ci, vp, sz, vp]
+    lib.gemm_workspace_bytes.restype = sz
+    lib.gemm_workspace_bytes.argtypes = [ci, i64, i64, i64, i64]
+    lib.gemm_strerror.restype = ctypes.c_char_p
+    lib.gemm_strerror.argtypes = [ci]
+    lib.gemm_last_hip_error.restype = ci
+    lib.gemm_last_hip_error.argtypes = []
+    lib.gemm_force_variant.restype = ci
+    lib.gemm_force_variant.argtypes = [ci, ci]
+    lib.gemm_variant_name.restype = ctypes.c_char_p
+    lib.gemm_variant_name.argtypes = [ci]
+    lib.gemm_last_variant.restype = ci
+    lib.gemm_last_variant.argtypes = []
+    lib.gemm_last_split.restype = ci
+    lib.gemm_last_split.argtypes = []
+    _lib = lib
+    return lib
+
+
+def _ptr(t):
+    if t is None:
+        return ctypes.c_void_p(0)
+    if isinstance(t, int):
+        return ctypes.c_void_p(t)
+    return ctypes.c_void_p(t.data_ptr())
+
+
+def _stream(stream):
+    if stream is None:
+        import torch
+        return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+    if isinstance(stream, int):
+        return ctypes.c_void_p(stream)
+    return ctypes.c_void_p(stream.cuda_stream)
+
+
+def _ws(workspace):
+    if workspace is None:
+        return ctypes.c_void_p(0), 0
+    return ctypes.c_void_p(workspace.data_ptr()), workspace.numel() * workspace.element_size()
+
+
+def _check(rc, where, check):
+    if check and rc != OK:
+        raise BrgemmError(rc, where)
+    return rc
+
+
+def gemm_f32(transA, transB, M, N, K, A, lda, B, ldb, beta, C, ldc, workspace=None, stream=None, check=True):
+    ws, nb = _ws(workspace)
+    rc = load().gemm_f32(transA, transB, M, N, K, _ptr(A), lda, _ptr(B), ldb, beta, _ptr(C), ldc,
+                         ws, nb, _stream(stream))
+    return _check(rc, "gemm_f32", check)
+
+
+def gemm_bf16(transA, transB, M, N, K, A, lda, B, ldb, beta, C, ldc, c_is_f32, workspace=None, stream=None,
+              check=True):
+    ws, nb = _ws(workspace)
+    rc = load().gemm_bf16(transA, transB, M, N, K, _ptr(A), lda, _ptr(B), ldb, beta, _ptr(C), ldc,
+                          int(bool(c_is_f32)), ws, nb, _stream(stream))
+    return _check(rc, "gemm_bf16", check)
+
+
+def brgemm_bf16(transA, transB, M, N, K, batch, A_base, A_off, lda, B_base, B_off, ldb, beta, C, ldc,
+                workspace=None, stream=None, check=True):
+    ws, nb = _ws(workspace)
+    rc = load().brgemm_bf16(transA, transB, M, N, K, batch, _ptr(A_base), _ptr(A_off), lda,
+                            _ptr(B_base), _ptr(B_off), ldb, beta, _ptr(C), ldc, ws, nb, _stream(stream))
+    return _check(rc, "brgemm_bf16", check)
+
+
+def brgemm_fused(in_dtype, transA, transB, M, N, K, batch, A_base, A_off, lda, B_base, B_off, ldb, beta,
+                 C, ldc, c_is_f32, bias, epilogue, workspace=None, stream=None, check=True):
+    ws, nb = _ws(workspace)
+    rc = load().brgemm_fused(in_dtype, transA, transB, M, N, K, batch, _ptr(A_base), _ptr(A_off), lda,
+                             _ptr(B_base), _ptr(B_off), ldb, beta, _ptr(C), ldc, int(bool(c_is_f32)),
+                             _ptr(bias), epilogue, ws, nb, _stream(stream))
+    return _check(rc, "brgemm_fused", check)
+
+
+def gemm_workspace_bytes(dtype, M, N, K, batch=1):
+    return int(load().gemm_workspace_bytes(dtype, M, N, K, batch))
+
+
+def strerror(code):
+    return load().gemm_strerror(code).decode()
+
+
+gemm_strerror = strerror
+
+
+def gemm_last_hip_error():
+    return int(load().gemm_last_hip_error())
+
+
+def gemm_force_variant(variant, split=0):
+    rc = load().gemm_force_variant(variant, split)
+    if rc != OK:
+        raise BrgemmError(rc, "gemm_force_variant")
+
+
+def gemm_variant_name(v):
+    return load().gemm_variant_name(v).decode()
+
+
+def variants():
+    """All variant names, indexed by variant number."""
+    out, v = [], 0
+    while True:
+        n = gemm_variant_name(v)
+        if not n:
+            return out
+        out.append(n)
+        v += 1
+
+
+def gemm_last_variant():
+    return int(load().gemm_last_variant())
+
+
+def gemm_last_split():
+    return int(load().gemm_last_split())

@@ -1,0 +1,209 @@
+// Host side of the C ABI (include/brgemm.h): argument validation, choice of
+// kernel variant and reduction split, launches on the caller's stream.
+// The library never allocates, frees or synchronises.
+#include "../../include/brgemm.h"
+#include "common.hpp"
+#include "variants.hpp"
+
+using namespace brg;
+
+namespace {
+
+thread_local int tl_last_hip_error = 0;
+thread_local int tl_forced_variant = -1;
+thread_local int tl_forced_split = 0;
+thread_local int tl_last_variant = -1;
+thread_local int tl_last_split = 0;
+
+inline int64_t stored_cols_a(const Problem &p) { return p.transA ? p.M : p.K; }
+inline int64_t stored_cols_b(const Problem &p) { return p.transB ? p.K : p.N; }
+
+constexpr int64_t kMaxDim = 2147483647LL;
+
+int validate(const Problem &p, const void *workspace, size_t workspace_bytes, bool need_offsets)
+{
+    if ((p.transA | 1) != 1 || (p.transB | 1) != 1)
+        return BRGEMM_INVALID_ARG;
+    if (p.M < 0 || p.N < 0 || p.K < 0 || p.batch < 0)
+        return BRGEMM_INVALID_ARG;
+    if (p.M > kMaxDim || p.N > kMaxDim || p.K > kMaxDim || p.batch > kMaxDim)
+        return BRGEMM_INVALID_ARG;
+    if (workspace_bytes > 0 && !workspace)
+        return BRGEMM_INVALID_ARG;
+    if (workspace && ((uintptr_t)workspace & 255u))
+        return BRGEMM_MISALIGNED_WORKSPACE;
+    if (p.M == 0 || p.N == 0)
+        return BRGEMM_OK;
+    if (!p.C || p.ldc < p.N)
+        return BRGEMM_INVALID_ARG;
+    if (p.K > 0 && p.batch > 0) {
+        if (!p.A || !p.B)
+            return BRGEMM_INVALID_ARG;
+        if (p.lda < stored_cols_a(p) || p.ldb < stored_cols_b(p))
+            return BRGEMM_INVALID_ARG;
+        if (need_offsets && (!p.A_off || !p.B_off))
+            return BRGEMM_INVALID_ARG;
+        if ((p.A_off == nullptr) != (p.B_off == nullptr))
+            return BRGEMM_INVALID_ARG;
+        if (!p.A_off && p.batch > 1)
+            return BRGEMM_INVALID_ARG;
+    }
+    return BRGEMM_OK;
+}
+
+int finish(hipError_t e)
+{
+    if (e != hipSuccess) {
+        tl_last_hip_error = (int)e;
+        return BRGEMM_HIP_ERROR;
+    }
+    return BRGEMM_OK;
+}
+
+int run(Problem &p, void *workspace, size_t workspace_bytes, bool need_offsets)
+{
+    int rc = validate(p, workspace, workspace_bytes, need_offsets);
+    if (rc != BRGEMM_OK)
+        return rc;
+    if (p.M == 0 || p.N == 0)
+        return BRGEMM_OK;
+    if (p.K == 0 || p.batch == 0) {
+        if (p.beta == 1.0f && !p.bias && !p.relu)
+            return BRGEMM_OK;               // C = 1*C: nothing to do
+        tl_last_variant = V_GENERIC;
+        tl_last_split = 1;
+        return finish(launch_scale_only(p));
+    }
+
+    Plan plan;
+    rc = choose_plan(p, workspace_bytes, tl_forced_variant, tl_forced_split, &plan);
+    if (rc != BRGEMM_OK)
+        return rc;
+    p.split = plan.split;
+    p.partial = plan.split > 1 ? (float *)workspace : nullptr;
+
+    hipError_t e = launch_variant(plan.variant, p);
+    if (e == hipSuccess && plan.split > 1)
+        e = launch_reduce(p);
+    if (e == hipSuccess) {
+        tl_last_variant = plan.variant;
+        tl_last_split = plan.split;
+    }
+    return finish(e);
+}
+
+}  // namespace
+
+extern "C" {
+
+int gemm_f32(int transA, int transB, int64_t M, int64_t N, int64_t K,
+             const float *A, int64_t lda, const float *B, int64_t ldb,
+             float beta, float *C, int64_t ldc,
+             void *workspace, size_t workspace_bytes, void *stream)
+{
+    Problem p{};
+    p.in_bf16 = 0; p.transA = transA; p.transB = transB;
+    p.M = M; p.N = N; p.K = K; p.batch = 1;
+    p.A = A; p.lda = lda; p.B = B; p.ldb = ldb;
+    p.beta = beta; p.C = C; p.ldc = ldc; p.c_f32 = 1;
+    p.stream = (hipStream_t)stream;
+    return run(p, workspace, workspace_bytes, false);
+}
+
+int gemm_bf16(int transA, int transB, int64_t M, int64_t N, int64_t K,
+              const uint16_t *A, int64_t lda, const uint16_t *B, int64_t ldb,
+              float beta, void *C, int64_t ldc, int c_is_f32,
+              void *workspace, size_t workspace_bytes, void *stream)
+{
+    Problem p{};
+    p.in_bf16 = 1; p.transA = transA; p.transB = transB;
+    p.M = M; p.N = N; p.K = K; p.batch = 1;
+    p.A = A; p.lda = lda; p.B = B; p.ldb = ldb;
+    p.beta = beta; p.C = C; p.ldc = ldc; p.c_f32 = c_is_f32 ? 1 : 0;
+    p.stream = (hipStream_t)stream;
+    return run(p, workspace, workspace_bytes, false);
+}
+
+int brgemm_bf16(int transA, int transB, int64_t M, int64_t N, int64_t K, int64_t batch,
+                const uint16_t *A_base, const int64_t *A_off, int64_t lda,
+                const uint16_t *B_base, const int64_t *B_off, int64_t ldb,
+                float beta, float *C, int64_t ldc,
+                void *workspace, size_t workspace_bytes, void *stream)
+{
+    Problem p{};
+    p.in_bf16 = 1; p.transA = transA; p.transB = transB;
+    p.M = M; p.N = N; p.K = K; p.batch = batch;
+    p.A = A_base; p.A_off = A_off; p.lda = lda;
+    p.B = B_base; p.B_off = B_off; p.ldb = ldb;
+    p.beta = beta; p.C = C; p.ldc = ldc; p.c_f32 = 1;
+    p.stream = (hipStream_t)stream;
+    return run(p, workspace, workspace_bytes, true);
+}
+
+int brgemm_fused(int in_dtype, int transA, int transB,
+                 int64_t M, int64_t N, int64_t K, int64_t batch,
+                 const void *A_base, const int64_t *A_off, int64_t lda,
+                 const void *B_base, const int64_t *B_off, int64_t ldb,
+                 float beta, void *C, int64_t ldc, int c_is_f32,
+                 const float *bias, int epilogue,
+                 void *workspace, size_t workspace_bytes, void *stream)
+{
+    if (in_dtype != BRGEMM_DTYPE_F32 && in_dtype != BRGEMM_DTYPE_BF16)
+        return BRGEMM_INVALID_ARG;
+    if (epilogue & ~(BRGEMM_EPI_BIAS | BRGEMM_EPI_RELU))
+        return BRGEMM_INVALID_ARG;
+    if ((epilogue & BRGEMM_EPI_BIAS) && !bias && N > 0)
+        return BRGEMM_INVALID_ARG;
+    if (in_dtype == BRGEMM_DTYPE_F32 && !c_is_f32)
+        return BRGEMM_INVALID_ARG;
+    Problem p{};
+    p.in_bf16 = in_dtype == BRGEMM_DTYPE_BF16; p.transA = transA; p.transB = transB;
+    p.M = M; p.N = N; p.K = K; p.batch = batch;
+    p.A = A_base; p.A_off = A_off; p.lda = lda;
+    p.B = B_base; p.B_off = B_off; p.ldb = ldb;
+    p.beta = beta; p.C = C; p.ldc = ldc; p.c_f32 = c_is_f32 ? 1 : 0;
+    p.bias = (epilogue & BRGEMM_EPI_BIAS) ? bias : nullptr;
+    p.relu = (epilogue & BRGEMM_EPI_RELU) ? 1 : 0;
+    p.stream = (hipStream_t)stream;
+    return run(p, workspace, workspace_bytes, false);
+}
+
+size_t gemm_workspace_bytes(int dtype, int64_t M, int64_t N, int64_t K, int64_t batch)
+{
+    (void)dtype;
+    if (M <= 0 || N <= 0 || K <= 0 || batch <= 0)
+        return 0;
+    return (size_t)kMaxSplit * (size_t)M * (size_t)N * sizeof(float);
+}
+
+const char *gemm_strerror(int code)
+{
+    switch (code) {
+    case BRGEMM_OK: return "success";
+    case BRGEMM_INVALID_ARG: return "invalid argument (negative size, leading dimension too small, bad flag or NULL operand)";
+    case BRGEMM_UNSUPPORTED: return "unsupported";
+    case BRGEMM_WORKSPACE_TOO_SMALL: return "workspace too small for the forced split";
+    case BRGEMM_HIP_ERROR: return "HIP launch error (see gemm_last_hip_error)";
+    case BRGEMM_MISALIGNED_WORKSPACE: return "workspace is not 256-byte aligned";
+    default: return "unknown error code";
+    }
+}
+
+int gemm_last_hip_error(void) { return tl_last_hip_error; }
+
+int gemm_force_variant(int variant, int split)
+{
+    if (variant >= V_COUNT)
+        return BRGEMM_INVALID_ARG;
+    if (split > kMaxSplit)
+        return BRGEMM_INVALID_ARG;
+    tl_forced_variant = variant < 0 ? -1 : variant;
+    tl_forced_split = split <= 0 ? 0 : split;
+    return BRGEMM_OK;
+}
+
+const char *gemm_variant_name(int v) { return variant_name(v); }
+int gemm_last_variant(void) { return tl_last_variant; }
+int gemm_last_split(void) { return tl_last_split; }
+
+}  // extern "C"

@@ -1,0 +1,97 @@
+// Shared declarations of the GPU library (host dispatch <-> kernel launchers).
+// Not part of the public interface; the public interface is include/brgemm.h.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+namespace brg {
+
+// One fully validated problem: C = act(beta*C + sum_i A_i x B_i + bias)
+// (input/output statement of Algorithm 1; Section 6 for bias and ReLU).
+struct Problem {
+    int in_bf16;            // 1: A, B are bf16 bit patterns; 0: fp32
+    int transA, transB;     // 1: stored transposed (K x M / N x K), row-major
+    int64_t M, N, K, batch;
+    const void *A;          // base of every A_i
+    const int64_t *A_off;   // device, batch element offsets, or nullptr (all zero)
+    int64_t lda;
+    const void *B;
+    const int64_t *B_off;
+    int64_t ldb;
+    float beta;
+    void *C;
+    int64_t ldc;
+    int c_f32;              // 1: C is fp32; 0: bf16
+    const float *bias;      // nullptr or N fp32 values
+    int relu;
+    // Reduction split: the flattened (batch x k-block) iteration space is cut into
+    // `split` contiguous ranges, one per blockIdx.z; split > 1 writes raw fp32
+    // partial tiles to `partial` (split x M x N, dense) and a second kernel sums
+    // them in a fixed order and applies the epilogue (deterministic).
+    int split;
+    float *partial;
+    hipStream_t stream;
+};
+
+// fp32 -> bf16, round to nearest even, NaN -> quiet NaN (Section 4.3: one
+// narrowing after the whole sum).
+__device__ __forceinline__ uint16_t f32_to_bf16_rne(float f)
+{
+    uint32_t u = __float_as_uint(f);
+    if ((u & 0x7fffffffu) > 0x7f800000u)
+        return (uint16_t)((u >> 16) | 0x0040u);
+    u += 0x7fffu + ((u >> 16) & 1u);
+    return (uint16_t)(u >> 16);
+}
+
+__device__ __forceinline__ float bf16_to_f32(uint16_t h)
+{
+    return __uint_as_float((uint32_t)h << 16);
+}
+
+// Epilogue parameters as the kernels see them.
+struct Epilogue {
+    float beta;
+    void *C;
+    int64_t ldc;
+    int c_f32;
+    const float *bias;
+    int relu;
+};
+
+// v = finished sum for element (m, n): apply beta*C_old, bias, ReLU (fp32) and
+// return the value to store.  beta == 0 never reads C.
+__device__ __forceinline__ float epilogue_value(const Epilogue &e, float v, int64_t m, int64_t n)
+{
+    if (e.beta != 0.0f) {
+        float old = e.c_f32 ? ((const float *)e.C)[m * e.ldc + n]
+                            : bf16_to_f32(((const uint16_t *)e.C)[m * e.ldc + n]);
+        v = fmaf(e.beta, old, v);
+    }
+    if (e.bias)
+        v += e.bias[n];
+    if (e.relu)
+        v = (v < 0.0f) ? 0.0f : v;      // NaN stays NaN (fmaxf would drop it)
+    return v;
+}
+
+__device__ __forceinline__ void epilogue_store(const Epilogue &e, float v, int64_t m, int64_t n)
+{
+    v = epilogue_value(e, v, m, n);
+    if (e.c_f32)
+        ((float *)e.C)[m * e.ldc + n] = v;
+    else
+        ((uint16_t *)e.C)[m * e.ldc + n] = f32_to_bf16_rne(v);
+}
+
+// ---- launchers (each returns the hipError_t of its launch) -------------------
+
+// General kernel: any shape, alignment, transposes, batch, split.
+hipError_t launch_generic(const Problem &p);
+// Sum `split` partial tiles and apply the epilogue.
+hipError_t launch_reduce(const Problem &p);
+// beta-only pass for K == 0 or batch == 0: C = act(beta*C + bias).
+hipError_t launch_scale_only(const Problem &p);
+
+}  // namespace brg

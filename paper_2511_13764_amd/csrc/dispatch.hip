@@ -1,0 +1,54 @@
+// Variant table, eligibility rules and the automatic plan.
+#include "../../include/brgemm.h"
+#include "variants.hpp"
+
+namespace brg {
+
+const char *variant_name(int v)
+{
+    switch (v) {
+    case V_GENERIC: return "generic_64x64x16_f32mfma";
+    default: return "";
+    }
+}
+
+bool variant_eligible(int v, const Problem &p)
+{
+    (void)p;
+    switch (v) {
+    case V_GENERIC: return true;
+    default: return false;
+    }
+}
+
+static size_t split_bytes(const Problem &p, int split)
+{
+    return split > 1 ? (size_t)split * (size_t)p.M * (size_t)p.N * sizeof(float) : 0;
+}
+
+int choose_plan(const Problem &p, size_t workspace_bytes, int forced_variant, int forced_split, Plan *out)
+{
+    Plan plan{V_GENERIC, 1};
+    if (forced_variant >= 0) {
+        if (forced_variant >= V_COUNT || !variant_eligible(forced_variant, p))
+            return BRGEMM_INVALID_ARG;
+        plan.variant = forced_variant;
+    }
+    if (forced_split > 0) {
+        plan.split = forced_split;
+        if (split_bytes(p, plan.split) > workspace_bytes)
+            return BRGEMM_WORKSPACE_TOO_SMALL;
+    }
+    *out = plan;
+    return BRGEMM_OK;
+}
+
+hipError_t launch_variant(int v, const Problem &p)
+{
+    switch (v) {
+    case V_GENERIC: return launch_generic(p);
+    default: return hipErrorInvalidValue;
+    }
+}
+
+}  // namespace brg

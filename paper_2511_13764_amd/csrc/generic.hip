@@ -1,0 +1,180 @@
+// General BRGEMM kernel for gfx950: any M, N, K, batch, leading dimensions,
+// alignment and transpose flags.  It is the slow-but-always-correct member of
+// the family; the tuned kernels take over when their alignment rules hold.
+//
+// Structure (Algorithm 1 of the paper, mapped to a GPU): one workgroup owns a
+// 64 x 64 sub-block of C; its four wavefronts each keep a 32 x 32 accumulator
+// tile in registers over the whole batch and K loops (Section 2.1, advantage
+// (1)), feed it with the fp32 MFMA v_mfma_f32_32x32x2_f32, and apply beta /
+// bias / ReLU / narrowing once at the end.  bf16 inputs are widened exactly to
+// fp32 when they are staged into LDS, so each product is exact in fp32 and the
+// sum is fp32 (the appendix listings: widen, multiply, add in f32).
+#include "common.hpp"
+
+namespace brg {
+
+typedef __attribute__((ext_vector_type(16))) float f32x16;
+
+constexpr int GT = 64;      // tile edge (M and N)
+constexpr int GK = 16;      // k-block
+constexpr int GPAD = 1;     // LDS row padding (floats)
+
+template <bool BF16>
+__device__ __forceinline__ float load_in(const void *p, int64_t idx)
+{
+    if (BF16)
+        return bf16_to_f32(((const uint16_t *)p)[idx]);
+    return ((const float *)p)[idx];
+}
+
+template <bool BF16>
+__global__ void __launch_bounds__(256)
+generic_kernel(int transA, int transB, int64_t M, int64_t N, int64_t K, int64_t batch,
+               const void *A, const int64_t *A_off, int64_t lda,
+               const void *B, const int64_t *B_off, int64_t ldb,
+               Epilogue epi, int split, float *partial)
+{
+    __shared__ float As[GK][GT + GPAD];     // [k][m]
+    __shared__ float Bs[GK][GT + GPAD];     // [k][n]
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63, wave = tid >> 6;
+    const int wm = wave >> 1, wn = wave & 1;
+    const int64_t m0 = (int64_t)blockIdx.y * GT;
+    const int64_t n0 = (int64_t)blockIdx.x * GT;
+
+    // Flattened iteration space: it = i * kblocks + kb, cut into `split` ranges.
+    const int64_t kblocks = (K + GK - 1) / GK;
+    const int64_t total = batch * kblocks;
+    const int64_t per = (total + split - 1) / split;
+    const int64_t it_begin = (int64_t)blockIdx.z * per;
+    const int64_t it_end = (it_begin + per < total) ? it_begin + per : total;
+
+    f32x16 acc;
+    for (int r = 0; r < 16; ++r)
+        acc[r] = 0.0f;
+
+    for (int64_t it = it_begin; it < it_end; ++it) {
+        const int64_t i = it / kblocks;
+        const int64_t k0 = (it - i * kblocks) * GK;
+        const int64_t ao = A_off ? A_off[i] : 0;
+        const int64_t bo = B_off ? B_off[i] : 0;
+
+        // Stage the A block (64 x 16) and the B block (16 x 64) into LDS, zero-filled
+        // outside the matrix.  Threads run along the operand's contiguous direction.
+        for (int e = tid; e < GT * GK; e += 256) {
+            int m, k;
+            if (transA) { m = e % GT; k = e / GT; } else { k = e % GK; m = e / GK; }
+            const int64_t gm = m0 + m, gk = k0 + k;
+            float v = 0.0f;
+            if (gm < M && gk < K)
+                v = load_in<BF16>(A, ao + (transA ? gk * lda + gm : gm * lda + gk));
+            As[k][m] = v;
+        }
+        for (int e = tid; e < GT * GK; e += 256) {
+            int n, k;
+            if (transB) { k = e % GK; n = e / GK; } else { n = e % GT; k = e / GT; }
+            const int64_t gn = n0 + n, gk = k0 + k;
+            float v = 0.0f;
+            if (gn < N && gk < K)
+                v = load_in<BF16>(B, bo + (transB ? gn * ldb + gk : gk * ldb + gn));
+            Bs[k][n] = v;
+        }
+        __syncthreads();
+
+        // v_mfma_f32_32x32x2_f32: lane l supplies A[row l%32][k = l/32] and
+        // B[k = l/32][col l%32].
+#pragma unroll
+        for (int kk = 0; kk < GK; kk += 2) {
+            const float a = As[kk + (lane >> 5)][wm * 32 + (lane & 31)];
+            const float b = Bs[kk + (lane >> 5)][wn * 32 + (lane & 31)];
+            acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a, b, acc, 0, 0, 0);
+        }
+        __syncthreads();
+    }
+
+    // Accumulator layout of the 32x32 MFMA: register r of lane l holds
+    // row 8*(r/4) + 4*(l/32) + r%4, column l%32.
+    const int64_t n = n0 + wn * 32 + (lane & 31);
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+        const int64_t m = m0 + wm * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
+        if (m < M && n < N) {
+            if (split > 1)
+                partial[((int64_t)blockIdx.z * M + m) * N + n] = acc[r];
+            else
+                epilogue_store(epi, acc[r], m, n);
+        }
+    }
+}
+
+__global__ void __launch_bounds__(256)
+reduce_kernel(int64_t M, int64_t N, int split, const float *partial, Epilogue epi)
+{
+    const int64_t total = M * N;
+    for (int64_t e = (int64_t)blockIdx.x * 256 + threadIdx.x; e < total; e += (int64_t)gridDim.x * 256) {
+        float s = partial[e];
+        for (int z = 1; z < split; ++z)
+            s += partial[(int64_t)z * total + e];
+        epilogue_store(epi, s, e / N, e % N);
+    }
+}
+
+__global__ void __launch_bounds__(256)
+scale_only_kernel(int64_t M, int64_t N, Epilogue epi)
+{
+    const int64_t total = M * N;
+    for (int64_t e = (int64_t)blockIdx.x * 256 + threadIdx.x; e < total; e += (int64_t)gridDim.x * 256)
+        epilogue_store(epi, 0.0f, e / N, e % N);
+}
+
+static Epilogue make_epilogue(const Problem &p)
+{
+    Epilogue e;
+    e.beta = p.beta;
+    e.C = p.C;
+    e.ldc = p.ldc;
+    e.c_f32 = p.c_f32;
+    e.bias = p.bias;
+    e.relu = p.relu;
+    return e;
+}
+
+hipError_t launch_generic(const Problem &p)
+{
+    dim3 grid((unsigned)((p.N + GT - 1) / GT), (unsigned)((p.M + GT - 1) / GT), (unsigned)p.split);
+    Epilogue e = make_epilogue(p);
+    if (p.in_bf16)
+        hipLaunchKernelGGL(generic_kernel<true>, grid, dim3(256), 0, p.stream, p.transA, p.transB, p.M, p.N,
+                           p.K, p.batch, p.A, p.A_off, p.lda, p.B, p.B_off, p.ldb, e, p.split, p.partial);
+    else
+        hipLaunchKernelGGL(generic_kernel<false>, grid, dim3(256), 0, p.stream, p.transA, p.transB, p.M, p.N,
+                           p.K, p.batch, p.A, p.A_off, p.lda, p.B, p.B_off, p.ldb, e, p.split, p.partial);
+    return hipGetLastError();
+}
+
+static unsigned elementwise_grid(int64_t total)
+{
+    int64_t g = (total + 255) / 256;
+    if (g > 256 * 16)
+        g = 256 * 16;
+    if (g < 1)
+        g = 1;
+    return (unsigned)g;
+}
+
+hipError_t launch_reduce(const Problem &p)
+{
+    hipLaunchKernelGGL(reduce_kernel, dim3(elementwise_grid(p.M * p.N)), dim3(256), 0, p.stream, p.M, p.N,
+                       p.split, p.partial, make_epilogue(p));
+    return hipGetLastError();
+}
+
+hipError_t launch_scale_only(const Problem &p)
+{
+    hipLaunchKernelGGL(scale_only_kernel, dim3(elementwise_grid(p.M * p.N)), dim3(256), 0, p.stream, p.M, p.N,
+                       make_epilogue(p));
+    return hipGetLastError();
+}
+
+}  // namespace brg

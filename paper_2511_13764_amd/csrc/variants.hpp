@@ -1,0 +1,32 @@
+// Kernel variants and the host-side plan (which variant, how many reduction
+// splits).  Tile selection is by hand-tuned rule, as in Section 5(a) of the
+// paper (tile sizes are chosen per target by sweeping).
+#pragma once
+#include "common.hpp"
+
+namespace brg {
+
+enum Variant {
+    V_GENERIC = 0,      // any shape / alignment, fp32 MFMA, 64x64 tile
+    V_COUNT
+};
+
+constexpr int kMaxSplit = 16;
+
+struct Plan {
+    int variant;
+    int split;
+};
+
+const char *variant_name(int v);
+
+// Pick variant and split for a validated, non-empty problem.  forced_variant < 0
+// and forced_split <= 0 mean automatic.  Returns a BRGEMM_* code.
+int choose_plan(const Problem &p, size_t workspace_bytes, int forced_variant, int forced_split, Plan *out);
+
+// True when `v` can run `p` (alignment and layout rules of the tuned kernels).
+bool variant_eligible(int v, const Problem &p);
+
+hipError_t launch_variant(int v, const Problem &p);
+
+}  // namespace brg

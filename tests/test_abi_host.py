@@ -1,0 +1,117 @@
+"""CPU-only checks of the C-ABI library: it loads, exports every symbol the header
+declares, and rejects bad arguments before any GPU work (no compute calls here)."""
+import os
+import re
+
+import pytest
+
+from paper_2511_13764_amd import binding as B
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared_functions():
+    text = open(os.path.join(ROOT, "include", "brgemm.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b([a-z_0-9]+)\s*\(", text)) - {"defined"})
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(B.LIB_PATH):
+        from paper_2511_13764_amd import build
+        build.build()
+    return B.load()
+
+
+def test_exports_every_declared_symbol(lib):
+    names = _declared_functions()
+    assert {"gemm_f32", "gemm_bf16", "brgemm_bf16", "brgemm_fused", "gemm_workspace_bytes",
+            "gemm_strerror"} <= set(names)
+    for n in names:
+        assert hasattr(lib, n), f"{n} declared in brgemm.h but not exported"
+    assert set(B.EXPORTS) == set(names)
+
+
+def test_strerror_and_variants(lib):
+    for code in (0, -1, -2, -3, -4, -5, -99):
+        assert isinstance(B.strerror(code), str) and B.strerror(code)
+    v = B.variants()
+    assert v and v[0].startswith("generic")
+    assert B.gemm_variant_name(len(v)) == ""
+
+
+P = 0x1000  # fake, never dereferenced: every call below is rejected or a no-op before launch
+
+
+@pytest.mark.parametrize("kw", [
+    dict(M=-1), dict(N=-1), dict(K=-1), dict(transA=2), dict(transB=-1),
+    dict(lda=7), dict(ldb=7), dict(ldc=7), dict(A=0), dict(B=0), dict(C=0),
+])
+def test_gemm_rejects_bad_arguments(lib, kw):
+    a = dict(transA=0, transB=0, M=8, N=8, K=8, A=P, lda=8, B=P, ldb=8, beta=0.0, C=P, ldc=8)
+    a.update(kw)
+    rc = B.gemm_f32(a["transA"], a["transB"], a["M"], a["N"], a["K"], a["A"], a["lda"], a["B"], a["ldb"],
+                    a["beta"], a["C"], a["ldc"], stream=0, check=False)
+    assert rc == B.INVALID_ARG
+    rc = B.gemm_bf16(a["transA"], a["transB"], a["M"], a["N"], a["K"], a["A"], a["lda"], a["B"], a["ldb"],
+                     a["beta"], a["C"], a["ldc"], 0, stream=0, check=False)
+    assert rc == B.INVALID_ARG
+
+
+def test_leading_dimension_follows_transpose_flag(lib):
+    # transA: stored K x M, so lda >= M (not K); transB: stored N x K, so ldb >= K.
+    assert B.gemm_f32(1, 0, 16, 8, 4, P, 8, P, 8, 0.0, P, 8, stream=0, check=False) == B.INVALID_ARG
+    assert B.gemm_f32(0, 1, 4, 8, 16, P, 16, P, 8, 0.0, P, 8, stream=0, check=False) == B.INVALID_ARG
+
+
+def test_empty_problems_are_no_ops(lib):
+    assert B.gemm_f32(0, 0, 0, 8, 8, 0, 8, 0, 8, 0.0, 0, 8, stream=0, check=False) == B.OK
+    assert B.gemm_f32(0, 0, 8, 0, 8, 0, 8, 0, 8, 0.0, 0, 8, stream=0, check=False) == B.OK
+    assert B.gemm_bf16(0, 0, 0, 0, 0, 0, 1, 0, 1, 1.0, 0, 1, 1, stream=0, check=False) == B.OK
+    # K == 0 with beta == 1: C = C, nothing to launch
+    assert B.gemm_f32(0, 0, 8, 8, 0, 0, 1, 0, 8, 1.0, P, 8, stream=0, check=False) == B.OK
+
+
+def test_brgemm_argument_rules(lib):
+    ok = dict(transA=0, transB=0, M=8, N=8, K=8, batch=2, A=P, Ao=P, lda=8, B=P, Bo=P, ldb=8, C=P, ldc=8)
+
+    def call(**kw):
+        a = dict(ok)
+        a.update(kw)
+        return B.brgemm_bf16(a["transA"], a["transB"], a["M"], a["N"], a["K"], a["batch"], a["A"], a["Ao"],
+                             a["lda"], a["B"], a["Bo"], a["ldb"], 1.0, a["C"], a["ldc"], stream=0, check=False)
+    assert call(batch=-1) == B.INVALID_ARG
+    assert call(Ao=0) == B.INVALID_ARG
+    assert call(Bo=0) == B.INVALID_ARG
+    assert call(batch=0) == B.OK            # C = 1*C
+    # fused entry: unknown dtype / flags, bias flag without bias, bf16 C with fp32 operands
+    f = lambda **kw: B.brgemm_fused(kw.get("dt", 1), 0, 0, 8, 8, 8, 1, P, 0, 8, P, 0, 8, 0.0, P, 8,
+                                    kw.get("cf32", 1), kw.get("bias", 0), kw.get("epi", 0), stream=0,
+                                    check=False)
+    assert f(dt=7) == B.INVALID_ARG
+    assert f(epi=8) == B.INVALID_ARG
+    assert f(epi=B.EPI_BIAS, bias=0) == B.INVALID_ARG
+    assert f(dt=0, cf32=0) == B.INVALID_ARG
+
+
+def test_workspace_rules(lib):
+    assert B.gemm_workspace_bytes(B.DTYPE_BF16, 0, 8, 8, 1) == 0
+    need = B.gemm_workspace_bytes(B.DTYPE_BF16, 128, 256, 64, 1)
+    assert need >= 2 * 128 * 256 * 4
+    lib = B.load()
+    import ctypes
+    # workspace_bytes > 0 with NULL pointer; misaligned workspace
+    rc = lib.gemm_f32(0, 0, 8, 8, 8, P, 8, P, 8, 0.0, P, 8, None, 1024, None)
+    assert rc == B.INVALID_ARG
+    rc = lib.gemm_f32(0, 0, 8, 8, 8, P, 8, P, 8, 0.0, P, 8, ctypes.c_void_p(0x1010), 1024, None)
+    assert rc == B.MISALIGNED_WORKSPACE
+    # forced split without enough workspace
+    B.gemm_force_variant(0, 4)
+    try:
+        rc = lib.gemm_f32(0, 0, 8, 8, 8, P, 8, P, 8, 0.0, P, 8, ctypes.c_void_p(0x1000), 256, None)
+        assert rc == B.WORKSPACE_TOO_SMALL
+    finally:
+        B.gemm_force_variant(-1, 0)
+    with pytest.raises(B.BrgemmError):
+        B.gemm_force_variant(10_000, 0)

@@ -1,0 +1,336 @@
+"""Parity of the HIP path with the CPU oracle, element by element, through the C ABI.
+
+Bars (relative Frobenius error against the fp64 oracle): fp32 <= 1e-5; bf16-in /
+fp32-accumulate / bf16-out <= 2e-3; bf16-in / fp32-out <= 1e-5.  Integer-valued
+inputs must match bit for bit (every partial sum is exact in fp32, whatever the
+order of summation).
+"""
+import sys
+
+import numpy as np
+import pytest
+import torch
+
+from paper_2511_13764_amd import binding as B
+from paper_2511_13764_amd import workloads as W
+
+import gpu_helpers as H
+
+pytestmark = pytest.mark.gpu
+
+
+def say(msg):
+    print(f"[gpu-case] {msg}", flush=True)
+    sys.stdout.flush()
+
+
+@pytest.fixture(scope="module", autouse=True)
+def _need_gpu():
+    assert torch.cuda.is_available(), "GPU tests need a GPU"
+    B.load()
+
+
+def _tol(case):
+    if case.dtype == "f32":
+        return H.TOL_F32
+    return H.TOL_BF16_F32OUT if case.c_is_f32 else H.TOL_BF16
+
+
+# ------------------------------------------------------------------ the named configurations
+
+def test_config1_f32_256(oracle):
+    case = W.config1_f32_256()
+    say(case.name)
+    out, _ = H.run_gemm_case(case)
+    ref = H.oracle_gemm_case(oracle, case)
+    err = H.rel_fro(H.widen(out), ref)
+    say(f"{case.name} rel_fro={err:.3e}")
+    assert err <= H.TOL_F32
+
+
+def test_config2_f32_2048_beta(oracle):
+    case = W.config2_f32_2048()
+    say(case.name)
+    out, _ = H.run_gemm_case(case, workspace_bytes=B.gemm_workspace_bytes(0, case.M, case.N, case.K))
+    ref = H.oracle_gemm_case(oracle, case)
+    err = H.rel_fro(H.widen(out), ref)
+    say(f"{case.name} rel_fro={err:.3e}")
+    assert err <= H.TOL_F32
+
+
+@pytest.mark.parametrize("size", [1024, 2048])
+def test_config3_bf16_square_full(oracle, size):
+    case = W.config3_bf16_square(size)
+    say(case.name)
+    out, _ = H.run_gemm_case(case, workspace_bytes=B.gemm_workspace_bytes(1, size, size, size))
+    ref = H.oracle_gemm_case(oracle, case)
+    err = H.rel_fro(H.widen(out), ref)
+    # second figure: against the oracle rounded once to bf16 (isolates kernel error)
+    err_out = H.rel_fro(H.widen(out), H.widen(oracle.round_to_out(ref, 1)))
+    say(f"{case.name} rel_fro={err:.3e} vs_rounded_oracle={err_out:.3e}")
+    assert err <= H.TOL_BF16
+    assert err_out <= 1e-3
+    # fp32-out variant of the same problem
+    case.c_is_f32 = True
+    out32, _ = H.run_gemm_case(case)
+    err32 = H.rel_fro(H.widen(out32), ref)
+    say(f"{case.name} fp32-out rel_fro={err32:.3e}")
+    assert err32 <= H.TOL_BF16_F32OUT
+
+
+@pytest.mark.parametrize("size", [4096, 8192])
+def test_config3_bf16_square_sampled(oracle, size):
+    """Full-size launch as the benchmark times it; the oracle computes sampled complete rows."""
+    case = W.config3_bf16_square(size)
+    say(case.name)
+    out, _ = H.run_gemm_case(case, workspace_bytes=B.gemm_workspace_bytes(1, size, size, size))
+    rows = H.sample_rows(size, 96 if size == 4096 else 48)
+    ref = H.oracle_gemm_case(oracle, case, rows=rows)
+    err = H.rel_fro(H.widen(out[rows]), ref)
+    say(f"{case.name} rows={len(rows)} rel_fro={err:.3e}")
+    assert err <= H.TOL_BF16
+    # column sample: every row, a few full columns, via the transposed problem (A B)^T = B^T A^T
+    cols = [0, 1, 255, 256, size // 2, size - 257, size - 1]
+    refT = oracle.gemm_ref(case.B, case.ldb, case.A, case.lda, size, size, size, transA=1, transB=1, rows=cols)
+    errc = H.rel_fro(H.widen(out[:, cols]).T, refT)
+    say(f"{case.name} cols={len(cols)} rel_fro={errc:.3e}")
+    assert errc <= H.TOL_BF16
+
+
+@pytest.mark.parametrize("which", ["up", "down"])
+@pytest.mark.parametrize("M", [16, 128, 4096])
+def test_config4_mlp_shapes(oracle, which, M):
+    case = W.config4_mlp(M, which)
+    say(case.name)
+    ws = B.gemm_workspace_bytes(1, case.M, case.N, case.K)
+    out, _ = H.run_gemm_case(case, workspace_bytes=min(ws, 1 << 30))
+    rows = None if M <= 128 else H.sample_rows(M, 40)
+    if M == 128:
+        rows = H.sample_rows(M, 48, seed=6)
+    ref = H.oracle_gemm_case(oracle, case, rows=rows)
+    got = H.widen(out if rows is None else out[rows])
+    err = H.rel_fro(got, ref)
+    say(f"{case.name} variant={B.gemm_variant_name(B.gemm_last_variant())} split={B.gemm_last_split()} "
+        f"rel_fro={err:.3e}")
+    assert err <= H.TOL_BF16
+    if M == 16:                      # fp32-out variant on the small one
+        case.c_is_f32 = True
+        out32, _ = H.run_gemm_case(case, workspace_bytes=ws)
+        assert H.rel_fro(H.widen(out32), ref) <= H.TOL_BF16_F32OUT
+
+
+def test_config5_brgemm_scattered_pool(oracle):
+    case = W.config5_brgemm()
+    say(case.name)
+    ws = B.gemm_workspace_bytes(1, case.M, case.N, case.K, case.batch)
+    out = H.run_brgemm_case(case, workspace_bytes=ws)
+    assert np.isfinite(out).all(), "a read strayed into the NaN canary between the tiles"
+    ref = H.oracle_brgemm_case(oracle, case)
+    err = H.rel_fro(out, ref)
+    say(f"{case.name} variant={B.gemm_variant_name(B.gemm_last_variant())} split={B.gemm_last_split()} "
+        f"rel_fro={err:.3e}")
+    assert err <= H.TOL_BF16_F32OUT
+    # without a workspace the library must still be right (no split possible)
+    out2 = H.run_brgemm_case(case, workspace_bytes=0)
+    assert H.rel_fro(out2, ref) <= H.TOL_BF16_F32OUT
+
+
+# ------------------------------------------------------------------ exactness on integer-valued inputs
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("tA,tB", [(0, 0), (0, 1), (1, 0), (1, 1)])
+@pytest.mark.parametrize("M,N,K", [(256, 256, 256), (257, 131, 67), (512, 768, 192), (33, 520, 1000)])
+def test_small_integer_bit_exact(oracle, dtype, tA, tB, M, N, K):
+    Al = W.small_int_matrix(10 + M, (M, K))
+    Bl = W.small_int_matrix(20 + N, (K, N))
+    As = np.ascontiguousarray(Al.T if tA else Al)
+    Bs = np.ascontiguousarray(Bl.T if tB else Bl)
+    if dtype == "bf16":
+        As, Bs = W.to_bf16_bits(As), W.to_bf16_bits(Bs)
+    case = W.GemmCase(f"int_{dtype}_{M}x{N}x{K}_t{tA}{tB}", dtype, M, N, K, tA, tB, 0.0, As, Bs, None, True)
+    say(case.name)
+    out, _ = H.run_gemm_case(case, ldc=N + 8)
+    ref = H.oracle_gemm_case(oracle, case)
+    assert np.array_equal(out.astype(np.float64), ref)
+
+
+# ------------------------------------------------------------------ ragged shapes, padded leading dimensions, misalignment
+
+@pytest.mark.parametrize("dtype,c_f32", [("f32", True), ("bf16", False), ("bf16", True)])
+@pytest.mark.parametrize("tA,tB", [(0, 0), (0, 1), (1, 0), (1, 1)])
+@pytest.mark.parametrize("M,N,K,pad", [(257, 131, 67, 3), (1, 1, 1, 0), (64, 64, 8, 8), (300, 260, 520, 8),
+                                       (129, 1000, 64, 16)])
+def test_ragged_and_padded(oracle, dtype, c_f32, tA, tB, M, N, K, pad):
+    ra, ca = (K, M) if tA else (M, K)
+    rb, cb = (N, K) if tB else (K, N)
+    A = np.full((ra, ca + pad), np.nan, np.float32)
+    Bm = np.full((rb, cb + pad), np.nan, np.float32)
+    A[:, :ca] = W.normal_f32(61, 0, (ra, ca))
+    Bm[:, :cb] = W.normal_f32(61, 1, (rb, cb))
+    C0 = W.normal_f32(61, 2, (M, N))
+    if dtype == "bf16":
+        A, Bm = W.to_bf16_bits(A), W.to_bf16_bits(Bm)
+    if not c_f32:
+        C0 = W.to_bf16_bits(C0)
+    case = W.GemmCase(f"ragged_{dtype}_{M}x{N}x{K}_t{tA}{tB}_pad{pad}", dtype, M, N, K, tA, tB, -0.75,
+                      A, Bm, C0, c_f32)
+    say(case.name)
+    out, _ = H.run_gemm_case(case, ldc=N + pad)
+    ref = H.oracle_gemm_case(oracle, case)
+    assert np.isfinite(H.widen(out)).all(), "padding (NaN) leaked into the result"
+    assert H.rel_fro(H.widen(out), ref) <= _tol(case)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_misaligned_bases(oracle, dtype):
+    """Operands that start one element into an allocation (2- or 4-byte alignment only)."""
+    M, N, K = 130, 260, 136
+    A = W.normal_f32(62, 0, (M * K + 1,))
+    Bm = W.normal_f32(62, 1, (K * N + 1,))
+    if dtype == "bf16":
+        A, Bm = W.to_bf16_bits(A), W.to_bf16_bits(Bm)
+    dA, dB = H.dev(A), H.dev(Bm)
+    dC = torch.full((M * N + 1,), float("nan"), dtype=torch.float32, device="cuda")
+    say(f"misaligned_{dtype}")
+    if dtype == "f32":
+        B.gemm_f32(0, 0, M, N, K, dA[1:], K, dB[1:], N, 0.0, dC[1:], N)
+    else:
+        B.gemm_bf16(0, 0, M, N, K, dA[1:], K, dB[1:], N, 0.0, dC[1:], N, 1)
+    torch.cuda.synchronize()
+    out = dC[1:].cpu().numpy().reshape(M, N)
+    ref = oracle.gemm_ref(A[1:].reshape(M, K), K, Bm[1:].reshape(K, N), N, M, N, K)
+    assert H.rel_fro(out, ref) <= 1e-5
+    assert np.isnan(dC[0].item())
+
+
+# ------------------------------------------------------------------ beta, NaN handling, empty problems
+
+def test_beta_zero_never_reads_c_and_nan_row(oracle):
+    M, N, K = 192, 320, 128
+    A = W.normal_bf16(63, 0, (M, K))
+    Bm = W.normal_bf16(63, 1, (K, N))
+    A[77, 5] = W.BF16_NAN
+    case = W.GemmCase("nan_row", "bf16", M, N, K, 0, 0, 0.0, A, Bm, None, True)
+    say(case.name)
+    out, _ = H.run_gemm_case(case)           # C pre-filled with NaN: beta == 0 must ignore it
+    assert np.isnan(out[77]).all()
+    assert np.isfinite(np.delete(out, 77, axis=0)).all()
+
+
+@pytest.mark.parametrize("beta", [1.0, 0.5, -2.0])
+@pytest.mark.parametrize("c_f32", [True, False])
+def test_beta_values(oracle, beta, c_f32):
+    M, N, K = 256, 384, 320
+    A = W.normal_bf16(64, 0, (M, K))
+    Bm = W.normal_bf16(64, 1, (N, K))
+    C0 = W.normal_f32(64, 2, (M, N), sigma=10.0)
+    if not c_f32:
+        C0 = W.to_bf16_bits(C0)
+    case = W.GemmCase(f"beta{beta}_cf32{c_f32}", "bf16", M, N, K, 0, 1, beta, A, Bm, C0, c_f32)
+    say(case.name)
+    out, _ = H.run_gemm_case(case)
+    ref = H.oracle_gemm_case(oracle, case)
+    assert H.rel_fro(H.widen(out), ref) <= _tol(case)
+
+
+def test_k_zero_and_batch_zero_scale_c(oracle):
+    M, N = 70, 90
+    C0 = W.normal_f32(65, 0, (M, N))
+    dC = H.dev(C0.copy())
+    dummy = torch.zeros(16, dtype=torch.float32, device="cuda")
+    say("k_zero")
+    B.gemm_f32(0, 0, M, N, 0, dummy, 1, dummy, N, 0.5, dC, N)
+    torch.cuda.synchronize()
+    assert np.array_equal(dC.cpu().numpy(), (np.float32(0.5) * C0))
+    B.gemm_f32(0, 0, M, N, 0, dummy, 1, dummy, N, 0.0, dC, N)
+    torch.cuda.synchronize()
+    assert (dC.cpu().numpy() == 0).all()
+    dC = H.dev(C0.copy())
+    off = torch.zeros(1, dtype=torch.int64, device="cuda")
+    B.brgemm_bf16(0, 0, M, N, 8, 0, dummy, off, 8, dummy, off, N, 2.0, dC, N)
+    torch.cuda.synchronize()
+    assert np.array_equal(dC.cpu().numpy(), np.float32(2.0) * C0)
+
+
+# ------------------------------------------------------------------ batch-reduce: small scattered cases, split, equivalence
+
+@pytest.mark.parametrize("tA,tB", [(0, 0), (0, 1), (1, 0), (1, 1)])
+@pytest.mark.parametrize("M,N,K,batch", [(32, 192, 32, 4), (64, 64, 64, 2), (100, 72, 24, 7), (128, 256, 64, 9)])
+def test_brgemm_small_scattered(oracle, tA, tB, M, N, K, batch):
+    # first two shapes: the bf16 listings of the paper (Section 2.2 listing; appendix bf16 kernels)
+    rng = np.random.default_rng(1234 + M + N + K + batch)
+    lda = (M if tA else K) + 8
+    ldb = (K if tB else N) + 8
+    a_rows, b_rows = (K if tA else M), (N if tB else K)
+    a_sz, b_sz = a_rows * lda, b_rows * ldb
+    slot = ((max(a_sz, b_sz) + 63) // 64 + 2) * 64
+    pool = np.full(slot * 2 * batch + 64, W.BF16_NAN, np.uint16)
+    order = rng.permutation(2 * batch)
+    A_off = order[:batch].astype(np.int64) * slot + 64
+    B_off = order[batch:].astype(np.int64) * slot + 64
+    for i in range(batch):
+        a = np.full((a_rows, lda), W.BF16_NAN, np.uint16)
+        b = np.full((b_rows, ldb), W.BF16_NAN, np.uint16)
+        a[:, :lda - 8] = W.normal_bf16(66, i, (a_rows, lda - 8))
+        b[:, :ldb - 8] = W.normal_bf16(66, 100 + i, (b_rows, ldb - 8))
+        pool[A_off[i]:A_off[i] + a_sz] = a.ravel()
+        pool[B_off[i]:B_off[i] + b_sz] = b.ravel()
+    C0 = W.normal_f32(66, 999, (M, N))
+    case = W.BrgemmCase(f"brgemm_small_{M}x{N}x{K}x{batch}_t{tA}{tB}", M, N, K, batch, tA, tB, 1.0,
+                        pool, A_off, B_off, lda, ldb, C0)
+    say(case.name)
+    ref = H.oracle_brgemm_case(oracle, case)
+    out = H.run_brgemm_case(case)
+    assert np.isfinite(out).all()
+    assert H.rel_fro(out, ref) <= H.TOL_BF16_F32OUT
+    # the same through a forced reduction split (partial tiles + fixed-order reduce)
+    ws = B.gemm_workspace_bytes(1, M, N, K, batch)
+    out_s = H.run_brgemm_case(case, workspace_bytes=ws, force=(0, 3))
+    assert H.rel_fro(out_s, ref) <= H.TOL_BF16_F32OUT
+    out_s2 = H.run_brgemm_case(case, workspace_bytes=ws, force=(0, 3))
+    assert np.array_equal(out_s, out_s2), "split reduction must be deterministic"
+
+
+def test_fused_bias_relu(oracle):
+    M, N, K = 200, 328, 264
+    for dtype, c_f32, tB in [("bf16", False, 1), ("bf16", True, 0), ("f32", True, 0)]:
+        A = W.normal_f32(67, 0, (M, K))
+        Bm = W.normal_f32(67, 1, (N, K) if tB else (K, N))
+        bias = W.normal_f32(67, 2, (N,))
+        if dtype == "bf16":
+            A, Bm = W.to_bf16_bits(A), W.to_bf16_bits(Bm)
+        case = W.GemmCase(f"bias_relu_{dtype}_cf32{c_f32}", dtype, M, N, K, 0, tB, 0.0, A, Bm, None, c_f32)
+        say(case.name)
+        out, _ = H.run_gemm_case(case, bias=bias, relu=True)
+        ref = H.oracle_gemm_case(oracle, case, bias=bias, relu=True)
+        assert (H.widen(out) >= 0).all()
+        assert ((H.widen(out) == 0) == (ref <= 0)).mean() > 0.999
+        assert H.rel_fro(H.widen(out), ref) <= _tol(case)
+        out_b, _ = H.run_gemm_case(case, bias=bias, relu=False)
+        ref_b = H.oracle_gemm_case(oracle, case, bias=bias, relu=False)
+        assert H.rel_fro(H.widen(out_b), ref_b) <= _tol(case)
+
+
+def test_every_variant_on_an_aligned_problem(oracle):
+    """Each kernel variant that accepts the problem, forced in turn, with and without a split."""
+    M, N, K = 512, 768, 512
+    for dtype in ("bf16", "f32"):
+        for tA, tB in [(0, 0), (0, 1), (1, 0), (1, 1)]:
+            Al = W.normal_f32(68, 0, (M, K))
+            Bl = W.normal_f32(68, 1, (K, N))
+            As = np.ascontiguousarray(Al.T if tA else Al)
+            Bs = np.ascontiguousarray(Bl.T if tB else Bl)
+            if dtype == "bf16":
+                As, Bs = W.to_bf16_bits(As), W.to_bf16_bits(Bs)
+            case = W.GemmCase(f"variants_{dtype}_t{tA}{tB}", dtype, M, N, K, tA, tB, 0.0, As, Bs, None, True)
+            ref = H.oracle_gemm_case(oracle, case)
+            ws = B.gemm_workspace_bytes(1, M, N, K)
+            for v, name in enumerate(B.variants()):
+                for split in (1, 2):
+                    say(f"{case.name} variant={name} split={split}")
+                    try:
+                        out, _ = H.run_gemm_case(case, workspace_bytes=ws, force=(v, split))
+                    except B.BrgemmError as e:
+                        assert e.code == B.INVALID_ARG      # variant does not take this dtype / layout
+                        continue
+                    assert H.rel_fro(H.widen(out), ref) <= 1e-5, (name, split)
