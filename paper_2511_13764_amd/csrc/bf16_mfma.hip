@@ -1,0 +1,513 @@
+// Tuned bf16 BRGEMM kernels for gfx950 (MI355X): bf16 operands, fp32 accumulation.
+//
+// Mapping of the paper's scheme (Algorithm 1; Sections 2.3 and 3.1) to CDNA4:
+//   microkernel  = one workgroup (4 wavefronts) owning a BM x BN block of C,
+//                  fed from LDS in 64-deep k-blocks;
+//   nanokernel   = one wavefront's (BM/2) x (BN/2) register tile, built from
+//                  v_mfma_f32_32x32x16_bf16 and kept in registers for the whole
+//                  batch and K loops (no spills: with a 128 x 128 wave tile the
+//                  accumulators take 256 of the 512 registers of a lane).
+//   "Flat" operands (Section 4.3): an operand whose contiguous direction is k
+//   feeds the matrix instruction with plain 128-bit LDS reads; one whose
+//   contiguous direction is m or n is re-laid-out on the way out of LDS with the
+//   transposing read ds_read_b64_tr_b16, overlapped with the MFMAs - the role the
+//   software-pipelined vpunpck packing plays in the paper's AMX kernels.
+//
+// Data movement: global -> LDS goes through global_load_lds_dwordx4 (16 bytes per
+// lane, no register staging).  One wave instruction fills 1 KiB of LDS in lane
+// order, so the swizzle that keeps the LDS reads bank-conflict free is applied by
+// choosing WHICH 16 global bytes each lane fetches.  Two LDS stages; the block
+// for k-step t+2 is requested while block t's last slice is being multiplied.
+#include "common.hpp"
+#include "variants.hpp"
+#include <type_traits>
+
+namespace brg {
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(16))) float f32x16;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
+typedef __attribute__((ext_vector_type(4))) short s16x4;
+typedef __attribute__((ext_vector_type(8))) short s16x8;
+
+#define LDS_AS __attribute__((address_space(3)))
+#define GLB_AS __attribute__((address_space(1)))
+
+constexpr int BK = 64;                  // k-block depth (elements) = 128 bytes of bf16
+
+struct Bf16Args {
+    int64_t M, N, K, batch;
+    const uint16_t *A;
+    const int64_t *A_off;
+    int64_t lda;
+    const uint16_t *B;
+    const int64_t *B_off;
+    int64_t ldb;
+    Epilogue epi;
+    int split;
+    float *partial;
+    int tiles_m, tiles_n;
+};
+
+// s_waitcnt immediates for gfx9-family encodings: vmcnt in bits [3:0] and [15:14],
+// expcnt [6:4], lgkmcnt [11:8].
+__device__ __forceinline__ void wait_vmcnt0() { __builtin_amdgcn_s_waitcnt(0x0F70); }
+__device__ __forceinline__ void wait_lgkmcnt0() { __builtin_amdgcn_s_waitcnt(0xC07F); }
+
+__device__ __forceinline__ void load16_to_lds(const uint16_t *g, uint32_t lds_byte, LDS_AS char *lds0)
+{
+    __builtin_amdgcn_global_load_lds((const GLB_AS void *)g, (LDS_AS void *)(lds0 + lds_byte), 16, 0, 0);
+}
+
+// ---------------------------------------------------------------------------
+// Operand tile whose contiguous direction is k ("K-major": A with transA == 0,
+// B with transB == 1).  LDS image: row r (an m or n index) takes 128 bytes; its
+// 16-byte chunk c (8 consecutive k) sits at chunk position c ^ (r & 7).
+// ---------------------------------------------------------------------------
+template <int ROWS>
+struct KMajorTile {
+    static constexpr int kInstr = ROWS / 8;          // wave-instructions per tile
+    static constexpr int kPerWave = kInstr / 4;
+
+    // Global element offset (relative to the tile's k-block origin) this lane fetches
+    // for wave-instruction j of wave w.  row_limit clamps ragged edges to a valid row.
+    __device__ static int64_t src_offset(int w, int j, int lane, int64_t row0, int64_t row_limit, int64_t ld)
+    {
+        const int g = w * kPerWave + j;
+        int64_t row = row0 + 8 * g + (lane >> 3);
+        row = row < row_limit ? row : row_limit - 1;
+        const int c = (lane & 7) ^ (lane >> 3);
+        return row * ld + 8 * c;
+    }
+    __device__ static uint32_t dst_byte(int w, int j) { return (uint32_t)(w * kPerWave + j) * 1024u; }
+
+    // Byte offset of the 8 k-values lane `lane` needs for MFMA tile `t` (32 rows) and
+    // k-slice ks (16 k): row t*32 + lane%32, chunk 2*ks + lane/32.
+    __device__ static uint32_t frag_byte(int row_base, int t, int ks, int lane)
+    {
+        const int r = row_base + t * 32 + (lane & 31);
+        const int c = 2 * ks + (lane >> 5);
+        return (uint32_t)(r * 128 + ((c ^ (r & 7)) << 4));
+    }
+    __device__ static bf16x8 read_frag(LDS_AS char *tile, int row_base, int t, int ks, int lane)
+    {
+        return *(LDS_AS bf16x8 *)(tile + frag_byte(row_base, t, ks, lane));
+    }
+};
+
+// ---------------------------------------------------------------------------
+// Operand tile whose contiguous direction is m or n ("MN-major": A with
+// transA == 1, B with transB == 0).  LDS image: k-row kr takes COLS*2 bytes; its
+// 16-byte chunk c (8 consecutive m/n) sits at chunk position c ^ ((kr & 3) << 2),
+// which spreads the four k-rows one transposing read touches over distinct banks.
+// ---------------------------------------------------------------------------
+template <int COLS>
+struct MNMajorTile {
+    static constexpr int kChunksPerRow = COLS / 8;
+    static constexpr int kRowBytes = COLS * 2;
+    static constexpr int kInstr = BK * kChunksPerRow / 64;
+    static constexpr int kPerWave = kInstr / 4;
+
+    __device__ static int64_t src_offset(int w, int j, int lane, int64_t col0, int64_t col_limit, int64_t ld)
+    {
+        const int idx = (w * kPerWave + j) * 64 + lane;
+        const int kr = idx / kChunksPerRow;
+        const int pc = idx % kChunksPerRow;
+        const int c = pc ^ ((kr & 3) << 2);
+        int64_t col = col0 + 8 * c;
+        col = col < col_limit ? col : col0;           // chunk wholly outside: any valid chunk
+        return (int64_t)kr * ld + col;
+    }
+    __device__ static uint32_t dst_byte(int w, int j) { return (uint32_t)(w * kPerWave + j) * 1024u; }
+
+    // ds_read_b64_tr_b16 works on blocks of 16 lanes: lane i of a block supplies the
+    // address of 4 consecutive columns (4*(i%4)..) of k-row (i/4) and receives, for
+    // column i, the 4 k-values of those rows.  Two reads give the 8 k-values of the
+    // MFMA operand: k = 8*(lane/32) + 4*rd + 0..3 within the 16-deep slice.
+    __device__ static bf16x8 read_frag(LDS_AS char *tile, int col_base, int t, int ks, int lane)
+    {
+        const int b = lane >> 4, i = lane & 15;
+        const int col = col_base + t * 32 + 16 * (b & 1) + 4 * (i & 3);
+        const int c = col >> 3;
+        const int within = (col & 7) * 2;
+        s16x4 v[2];
+#pragma unroll
+        for (int rd = 0; rd < 2; ++rd) {
+            const int kr = ks * 16 + 8 * (b >> 1) + 4 * rd + (i >> 2);
+            const uint32_t byte = (uint32_t)(kr * kRowBytes + ((c ^ ((kr & 3) << 2)) << 4) + within);
+            v[rd] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((LDS_AS s16x4 *)(tile + byte));
+        }
+        s16x8 r = __builtin_shufflevector(v[0], v[1], 0, 1, 2, 3, 4, 5, 6, 7);
+        return __builtin_bit_cast(bf16x8, r);
+    }
+};
+
+template <int EXTENT, bool KMAJ>
+struct TileOf;
+template <int EXTENT>
+struct TileOf<EXTENT, true> { typedef KMajorTile<EXTENT> type; };
+template <int EXTENT>
+struct TileOf<EXTENT, false> { typedef MNMajorTile<EXTENT> type; };
+
+// XCD-aware tile order.  Workgroups are dealt round-robin to the 8 XCDs (each with
+// its own L2), so workgroup w is renumbered to t = (w % 8) * (T/8) + w / 8: every
+// XCD then owns a contiguous run of logical tiles, and logical tiles are walked in
+// groups of GM tile-rows so that a run shares few A row-panels and B column-panels.
+__device__ __forceinline__ void tile_coords(int w, int tiles_m, int tiles_n, int &tm, int &tn)
+{
+    const int T = tiles_m * tiles_n;
+    const int T8 = T & ~7;
+    int t = w;
+    if (w < T8)
+        t = (w & 7) * (T8 >> 3) + (w >> 3);
+    constexpr int GM = 4;
+    const int per_group = GM * tiles_n;
+    const int group = t / per_group;
+    const int first_m = group * GM;
+    const int gsize = (tiles_m - first_m) < GM ? (tiles_m - first_m) : GM;
+    const int in_group = t - group * per_group;
+    tm = first_m + in_group % gsize;
+    tn = in_group / gsize;
+}
+
+template <int I, int N, typename F>
+__device__ __forceinline__ void static_for(F &&f)
+{
+    if constexpr (I < N) {
+        f(std::integral_constant<int, I>{});
+        static_for<I + 1, N>(f);
+    }
+}
+
+// Four consecutive columns n..n+3 of row m, values already final sums.  `left` is
+// N - n (columns that exist); `vec` says 16-byte (fp32) / 8-byte (bf16) accesses
+// are aligned.
+__device__ __forceinline__ void store4_partial(float *dst, int64_t left, bool vec, float v0, float v1, float v2,
+                                               float v3)
+{
+    if (left <= 0)
+        return;
+    if (vec && left >= 4) {
+        *(f32x4 *)dst = f32x4{v0, v1, v2, v3};
+    } else {
+        dst[0] = v0;
+        if (left > 1) dst[1] = v1;
+        if (left > 2) dst[2] = v2;
+        if (left > 3) dst[3] = v3;
+    }
+}
+
+__device__ __forceinline__ void store4_epilogue(const Epilogue &e, int64_t m, int64_t n, int64_t left, bool vec,
+                                                float v0, float v1, float v2, float v3)
+{
+    if (left <= 0)
+        return;
+    if (!(vec && left >= 4)) {
+        epilogue_store(e, v0, m, n);
+        if (left > 1) epilogue_store(e, v1, m, n + 1);
+        if (left > 2) epilogue_store(e, v2, m, n + 2);
+        if (left > 3) epilogue_store(e, v3, m, n + 3);
+        return;
+    }
+    if (e.beta != 0.0f) {
+        if (e.c_f32) {
+            const f32x4 old = *(const f32x4 *)((const float *)e.C + m * e.ldc + n);
+            v0 = fmaf(e.beta, old[0], v0);
+            v1 = fmaf(e.beta, old[1], v1);
+            v2 = fmaf(e.beta, old[2], v2);
+            v3 = fmaf(e.beta, old[3], v3);
+        } else {
+            const uint2 old = *(const uint2 *)((const uint16_t *)e.C + m * e.ldc + n);
+            v0 = fmaf(e.beta, __uint_as_float(old.x << 16), v0);
+            v1 = fmaf(e.beta, __uint_as_float(old.x & 0xffff0000u), v1);
+            v2 = fmaf(e.beta, __uint_as_float(old.y << 16), v2);
+            v3 = fmaf(e.beta, __uint_as_float(old.y & 0xffff0000u), v3);
+        }
+    }
+    if (e.bias) {
+        const f32x4 bv = *(const f32x4 *)(e.bias + n);     // n is a multiple of 4; bias from hipMalloc
+        v0 += bv[0]; v1 += bv[1]; v2 += bv[2]; v3 += bv[3];
+    }
+    if (e.relu) {
+        v0 = v0 < 0.0f ? 0.0f : v0;
+        v1 = v1 < 0.0f ? 0.0f : v1;
+        v2 = v2 < 0.0f ? 0.0f : v2;
+        v3 = v3 < 0.0f ? 0.0f : v3;
+    }
+    if (e.c_f32) {
+        *(f32x4 *)((float *)e.C + m * e.ldc + n) = f32x4{v0, v1, v2, v3};
+    } else {
+        uint2 out;
+        out.x = (uint32_t)f32_to_bf16_rne(v0) | ((uint32_t)f32_to_bf16_rne(v1) << 16);
+        out.y = (uint32_t)f32_to_bf16_rne(v2) | ((uint32_t)f32_to_bf16_rne(v3) << 16);
+        *(uint2 *)((uint16_t *)e.C + m * e.ldc + n) = out;
+    }
+}
+
+template <int BM, int BN, bool A_KMAJ, bool B_KMAJ>
+__global__ void __launch_bounds__(256)
+bf16_mfma_kernel(Bf16Args p)
+{
+    typedef typename TileOf<BM, A_KMAJ>::type ATile;
+    typedef typename TileOf<BN, B_KMAJ>::type BTile;
+    constexpr int WM = BM / 2, WN = BN / 2;         // wave tile
+    constexpr int TM = WM / 32, TN = WN / 32;       // MFMA tiles per wave tile
+    constexpr uint32_t A_BYTES = BM * BK * 2, B_BYTES = BN * BK * 2;
+    constexpr uint32_t STAGE = A_BYTES + B_BYTES;
+
+    extern __shared__ __attribute__((aligned(1024))) char smem_generic[];
+    LDS_AS char *smem = (LDS_AS char *)smem_generic;
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wm = w >> 1, wn = w & 1;
+
+    int tm, tn;
+    tile_coords(blockIdx.x, p.tiles_m, p.tiles_n, tm, tn);
+    const int64_t m0 = (int64_t)tm * BM, n0 = (int64_t)tn * BN;
+
+    // Reduction range of this workgroup: flattened (batch, k-block) iterations
+    // (the host guarantees batch * K/64 < 2^31).
+    const int kblocks = (int)(p.K / BK);
+    const int total = (int)p.batch * kblocks;
+    const int per = (total + p.split - 1) / p.split;
+    const int it_begin = (int)blockIdx.y * per;
+    const int it_end = (it_begin + per < total) ? it_begin + per : total;
+    const int n_iter = it_end - it_begin;
+
+    // Per-lane global source offsets (elements), fixed for the whole kernel.
+    int64_t a_src[ATile::kPerWave], b_src[BTile::kPerWave];
+#pragma unroll
+    for (int j = 0; j < ATile::kPerWave; ++j)
+        a_src[j] = ATile::src_offset(w, j, lane, m0, p.M, p.lda);
+#pragma unroll
+    for (int j = 0; j < BTile::kPerWave; ++j)
+        b_src[j] = BTile::src_offset(w, j, lane, n0, p.N, p.ldb);
+    const int64_t a_kstep = A_KMAJ ? (int64_t)BK : (int64_t)BK * p.lda;
+    const int64_t b_kstep = B_KMAJ ? (int64_t)BK : (int64_t)BK * p.ldb;
+
+    // Load cursor: the (batch index, k-block) of the next block to request, and the
+    // operand pointers that go with it.  Advanced without divisions.
+    int ld_i = n_iter > 0 ? it_begin / kblocks : 0;
+    int ld_kb = n_iter > 0 ? it_begin - ld_i * kblocks : 0;
+    const uint16_t *ld_a = p.A + (p.A_off ? p.A_off[ld_i] : 0) + ld_kb * a_kstep;
+    const uint16_t *ld_b = p.B + (p.B_off ? p.B_off[ld_i] : 0) + ld_kb * b_kstep;
+    // Tile offsets live in device memory, so their alignment cannot be checked on the
+    // host: if any A_off / B_off is not a multiple of 8 elements (16 bytes) the whole
+    // workgroup stages its blocks through registers with 2-byte loads instead.
+    bool direct = true;
+    if (p.A_off) {
+        int ok = 1;
+        for (int i = tid; i < (int)p.batch; i += 256)
+            ok &= (((p.A_off[i] | p.B_off[i]) & 7) == 0);
+        direct = __syncthreads_and(ok) != 0;
+    }
+    auto staged16 = [&](const uint16_t *g, uint32_t lds_byte) {
+        s16x8 v;
+#pragma unroll
+        for (int e = 0; e < 8; ++e)
+            v[e] = (short)g[e];
+        *(LDS_AS s16x8 *)(smem + lds_byte + lane * 16) = v;
+    };
+    auto issue_loads = [&](int stage) {
+        const uint32_t base = (uint32_t)stage * STAGE;
+        if (direct) {
+#pragma unroll
+            for (int j = 0; j < ATile::kPerWave; ++j)
+                load16_to_lds(ld_a + a_src[j], base + ATile::dst_byte(w, j), smem);
+#pragma unroll
+            for (int j = 0; j < BTile::kPerWave; ++j)
+                load16_to_lds(ld_b + b_src[j], base + A_BYTES + BTile::dst_byte(w, j), smem);
+        } else {
+#pragma unroll
+            for (int j = 0; j < ATile::kPerWave; ++j)
+                staged16(ld_a + a_src[j], base + ATile::dst_byte(w, j));
+#pragma unroll
+            for (int j = 0; j < BTile::kPerWave; ++j)
+                staged16(ld_b + b_src[j], base + A_BYTES + BTile::dst_byte(w, j));
+        }
+        if (++ld_kb == kblocks) {
+            ld_kb = 0;
+            ++ld_i;
+            if (p.A_off && ld_i < (int)p.batch) {
+                ld_a = p.A + p.A_off[ld_i];
+                ld_b = p.B + p.B_off[ld_i];
+            }
+        } else {
+            ld_a += a_kstep;
+            ld_b += b_kstep;
+        }
+    };
+
+    f32x16 acc[TN][TM];
+#pragma unroll
+    for (int a = 0; a < TN; ++a)
+#pragma unroll
+        for (int b = 0; b < TM; ++b)
+#pragma unroll
+            for (int r = 0; r < 16; ++r)
+                acc[a][b][r] = 0.0f;
+
+    bf16x8 fa[2][TM], fb[2][TN];
+    auto read_frags = [&](int stage, int ks, int buf) {
+        LDS_AS char *at = smem + (uint32_t)stage * STAGE;
+        LDS_AS char *bt = at + A_BYTES;
+#pragma unroll
+        for (int t = 0; t < TM; ++t)
+            fa[buf][t] = ATile::read_frag(at, wm * WM, t, ks, lane);
+#pragma unroll
+        for (int t = 0; t < TN; ++t)
+            fb[buf][t] = BTile::read_frag(bt, wn * WN, t, ks, lane);
+    };
+    // Operands are passed swapped (B fragment first) so that the 32x32 result tile is
+    // C^T: lane l then owns row m = l%32 and, per group of 4 registers, 4 consecutive
+    // columns n - which makes the epilogue's stores 8 or 16 bytes per lane.
+    auto mma = [&](int buf) {
+#pragma unroll
+        for (int a = 0; a < TN; ++a)
+#pragma unroll
+            for (int b = 0; b < TM; ++b)
+                acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[buf][a], fa[buf][b], acc[a][b], 0, 0, 0);
+    };
+
+    if (n_iter > 0) {
+        issue_loads(0);
+        wait_vmcnt0();
+        __syncthreads();
+        if (n_iter > 1)
+            issue_loads(1);
+        read_frags(0, 0, 0);
+
+        // Steady state; the last block is peeled so that the loop body has no branch
+        // around the barrier (the same peeling the paper applies to its pipelined
+        // packing loop).  Order inside one block: slices 0-2 multiply while the next
+        // slice's fragments are read; before slice 3 is multiplied the barrier proves
+        // block it+1 complete and block `it` fully read, then the request for block
+        // it+2 and the first fragment reads of block it+1 are issued, and slice 3's
+        // MFMAs cover their latency.
+        for (int it = 0; it < n_iter - 1; ++it) {
+            const int cur = it & 1;
+            read_frags(cur, 1, 1);
+            mma(0);
+            read_frags(cur, 2, 0);
+            mma(1);
+            read_frags(cur, 3, 1);
+            mma(0);
+            wait_vmcnt0();
+            wait_lgkmcnt0();
+            __syncthreads();
+            __builtin_amdgcn_sched_barrier(0);
+            if (it + 2 < n_iter)
+                issue_loads(cur);
+            read_frags(cur ^ 1, 0, 0);
+            mma(1);
+        }
+        {
+            const int cur = (n_iter - 1) & 1;
+            read_frags(cur, 1, 1);
+            mma(0);
+            read_frags(cur, 2, 0);
+            mma(1);
+            read_frags(cur, 3, 1);
+            mma(0);
+            mma(1);
+        }
+    }
+
+    // ---- epilogue: beta*C, bias, ReLU, narrowing, store (or raw partial for a split)
+    // Every accumulator index below is a compile-time constant (static_for), so the
+    // tile never leaves the register file.
+    const int64_t m_base = m0 + wm * WM + (lane & 31);
+    const int64_t n_base = n0 + wn * WN + 4 * (lane >> 5);
+    if (p.split > 1) {
+        float *part = p.partial + (int64_t)blockIdx.y * p.M * p.N;
+        const bool vec = (p.N & 3) == 0;
+        static_for<0, TM>([&](auto bc) {
+            constexpr int b = decltype(bc)::value;
+            const int64_t m = m_base + b * 32;
+            if (m < p.M) {
+                static_for<0, TN * 4>([&](auto aq) {
+                    constexpr int a = decltype(aq)::value / 4, q = decltype(aq)::value % 4;
+                    const int64_t n = n_base + a * 32 + q * 8;
+                    store4_partial(part + m * p.N + n, p.N - n, vec, acc[a][b][4 * q + 0], acc[a][b][4 * q + 1],
+                                   acc[a][b][4 * q + 2], acc[a][b][4 * q + 3]);
+                });
+            }
+        });
+    } else {
+        const bool vec = (p.epi.ldc & 3) == 0 && (((uintptr_t)p.epi.C) & 15) == 0;
+        static_for<0, TM>([&](auto bc) {
+            constexpr int b = decltype(bc)::value;
+            const int64_t m = m_base + b * 32;
+            if (m < p.M) {
+                static_for<0, TN * 4>([&](auto aq) {
+                    constexpr int a = decltype(aq)::value / 4, q = decltype(aq)::value % 4;
+                    const int64_t n = n_base + a * 32 + q * 8;
+                    store4_epilogue(p.epi, m, n, p.N - n, vec, acc[a][b][4 * q + 0], acc[a][b][4 * q + 1],
+                                    acc[a][b][4 * q + 2], acc[a][b][4 * q + 3]);
+                });
+            }
+        });
+    }
+}
+
+// ---------------------------------------------------------------------------
+
+template <int BM, int BN>
+static hipError_t launch_tile(const Problem &p)
+{
+    Bf16Args a;
+    a.M = p.M; a.N = p.N; a.K = p.K; a.batch = p.batch;
+    a.A = (const uint16_t *)p.A; a.A_off = p.A_off; a.lda = p.lda;
+    a.B = (const uint16_t *)p.B; a.B_off = p.B_off; a.ldb = p.ldb;
+    a.epi.beta = p.beta; a.epi.C = p.C; a.epi.ldc = p.ldc; a.epi.c_f32 = p.c_f32;
+    a.epi.bias = p.bias; a.epi.relu = p.relu;
+    a.split = p.split; a.partial = p.partial;
+    a.tiles_m = (int)((p.M + BM - 1) / BM);
+    a.tiles_n = (int)((p.N + BN - 1) / BN);
+    const dim3 grid((unsigned)(a.tiles_m * a.tiles_n), (unsigned)p.split);
+    const size_t lds = 2 * (size_t)(BM + BN) * BK * 2;
+    const bool ak = p.transA == 0, bk = p.transB == 1;
+    void (*kern)(Bf16Args) = nullptr;
+    if (ak && bk) kern = bf16_mfma_kernel<BM, BN, true, true>;
+    else if (ak && !bk) kern = bf16_mfma_kernel<BM, BN, true, false>;
+    else if (!ak && bk) kern = bf16_mfma_kernel<BM, BN, false, true>;
+    else kern = bf16_mfma_kernel<BM, BN, false, false>;
+    static thread_local const void *configured[8] = {nullptr};
+    bool done = false;
+    for (const void *c : configured)
+        done = done || c == (const void *)kern;
+    if (!done) {
+        hipError_t e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e != hipSuccess)
+            return e;
+        for (auto &c : configured)
+            if (!c) { c = (const void *)kern; break; }
+    }
+    hipLaunchKernelGGL(kern, grid, dim3(256), lds, p.stream, a);
+    return hipGetLastError();
+}
+
+hipError_t launch_bf16_256x256(const Problem &p) { return launch_tile<256, 256>(p); }
+hipError_t launch_bf16_128x128(const Problem &p) { return launch_tile<128, 128>(p); }
+
+// Alignment and shape rules of the kernels in this file.
+bool bf16_mfma_eligible(const Problem &p)
+{
+    if (!p.in_bf16)
+        return false;
+    if (p.K % BK != 0)
+        return false;
+    if (((uintptr_t)p.A & 15) || ((uintptr_t)p.B & 15) || (p.lda & 7) || (p.ldb & 7))
+        return false;
+    if (p.transA == 1 && (p.M & 7))
+        return false;
+    if (p.transB == 0 && (p.N & 7))
+        return false;
+    if (p.batch * (p.K / BK) >= ((int64_t)1 << 31) || p.M * p.N >= ((int64_t)1 << 40))
+        return false;
+    return true;
+}
+
+}  // namespace brg

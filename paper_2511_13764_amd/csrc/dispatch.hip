@@ -8,15 +8,18 @@ const char *variant_name(int v)
 {
     switch (v) {
     case V_GENERIC: return "generic_64x64x16_f32mfma";
+    case V_BF16_256x256: return "bf16_256x256x64";
+    case V_BF16_128x128: return "bf16_128x128x64";
     default: return "";
     }
 }
 
 bool variant_eligible(int v, const Problem &p)
 {
-    (void)p;
     switch (v) {
     case V_GENERIC: return true;
+    case V_BF16_256x256:
+    case V_BF16_128x128: return bf16_mfma_eligible(p);
     default: return false;
     }
 }
@@ -29,6 +32,10 @@ static size_t split_bytes(const Problem &p, int split)
 int choose_plan(const Problem &p, size_t workspace_bytes, int forced_variant, int forced_split, Plan *out)
 {
     Plan plan{V_GENERIC, 1};
+    if (bf16_mfma_eligible(p)) {
+        const int64_t t256 = ((p.M + 255) / 256) * ((p.N + 255) / 256);
+        plan.variant = t256 >= 200 ? V_BF16_256x256 : V_BF16_128x128;
+    }
     if (forced_variant >= 0) {
         if (forced_variant >= V_COUNT || !variant_eligible(forced_variant, p))
             return BRGEMM_INVALID_ARG;
@@ -47,6 +54,8 @@ hipError_t launch_variant(int v, const Problem &p)
 {
     switch (v) {
     case V_GENERIC: return launch_generic(p);
+    case V_BF16_256x256: return launch_bf16_256x256(p);
+    case V_BF16_128x128: return launch_bf16_128x128(p);
     default: return hipErrorInvalidValue;
     }
 }

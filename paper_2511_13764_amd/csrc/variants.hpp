@@ -8,6 +8,8 @@ namespace brg {
 
 enum Variant {
     V_GENERIC = 0,      // any shape / alignment, fp32 MFMA, 64x64 tile
+    V_BF16_256x256,     // bf16, 256x256x64 workgroup tile, 128x128 wave tile
+    V_BF16_128x128,     // bf16, 128x128x64 workgroup tile, 64x64 wave tile
     V_COUNT
 };
 
@@ -28,5 +30,10 @@ int choose_plan(const Problem &p, size_t workspace_bytes, int forced_variant, in
 bool variant_eligible(int v, const Problem &p);
 
 hipError_t launch_variant(int v, const Problem &p);
+
+// bf16_mfma.hip
+bool bf16_mfma_eligible(const Problem &p);
+hipError_t launch_bf16_256x256(const Problem &p);
+hipError_t launch_bf16_128x128(const Problem &p);
 
 }  // namespace brg
