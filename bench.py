@@ -1,0 +1,175 @@
+#!/usr/bin/env python3
+"""Benchmark of the GEMM / BRGEMM hot path on one MI355X.
+
+One "step" is one pass of the whole hot path (tile decomposition, operand staging,
+MFMA loop, epilogue) over the headline workload: bf16-in / fp32-accumulate /
+bf16-out GEMM with M = N = K = 4096, row-major, beta = 0, inputs N(0,1) rounded to
+bf16 and already resident in HBM.  Prints ONE JSON line with the whole-job TFLOP/s,
+the MFMA roofline of the kernel (HIP-event duration of the same launches) and the
+CPU oracle timed on a bounded sample of the same workload.  Other configurations
+(fp32 2048^3, MLP shapes, skinny M, batch-reduce) are timed too and reported under
+"others" in the same line.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+METRIC = "GEMM TFLOP/s and % of MFMA peak (fp32, bf16), 4096^3 and MLP shapes"
+PEAK_BF16 = 2516.6      # TFLOP/s, dense bf16 MFMA: 256 CUs x 4096 flop/clk x 2.4 GHz
+PEAK_F32 = 157.3        # TFLOP/s, fp32 MFMA
+HBM_TBS = 8.0
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--no-others", action="store_true", help="time the headline workload only")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle leg")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU; --gpus must be 1 "
+              "(a multi-GPU job would shard M or N with no exchange, see DESIGN.md)", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    from paper_2511_13764_amd import binding as B
+    from paper_2511_13764_amd import workloads as W
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    B.load()
+
+    def dev(x):
+        return torch.from_numpy(x.view(np.int16) if x.dtype == np.uint16 else x).cuda()
+
+    def time_launches(fn, steps, warmup):
+        """Wall time per step (sync on both sides) and HIP-event time per launch."""
+        for _ in range(warmup):
+            fn()
+        torch.cuda.synchronize()
+        e0 = torch.cuda.Event(enable_timing=True)
+        e1 = torch.cuda.Event(enable_timing=True)
+        t0 = time.perf_counter()
+        e0.record()
+        for _ in range(steps):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        wall = (time.perf_counter() - t0) / steps
+        return wall, e0.elapsed_time(e1) * 1e-3 / steps
+
+    # ------------------------------------------------------------------ headline: bf16 4096^3
+    case = W.config3_bf16_square(4096)
+    M, N, K = case.M, case.N, case.K
+    dA, dB = dev(case.A), dev(case.B)
+    dC = torch.empty((M, N), dtype=torch.int16, device="cuda")
+    ws_bytes = B.gemm_workspace_bytes(B.DTYPE_BF16, M, N, K)
+    ws = torch.empty(min(ws_bytes, 1 << 30), dtype=torch.uint8, device="cuda")
+
+    def step():
+        B.gemm_bf16(0, 0, M, N, K, dA, K, dB, N, 0.0, dC, N, 0, workspace=ws)
+
+    wall, ev = time_launches(step, args.steps, args.warmup)
+    variant = B.gemm_variant_name(B.gemm_last_variant())
+    split = B.gemm_last_split()
+    flops = 2.0 * M * N * K
+    value = flops / wall / 1e12
+    achieved = flops / ev / 1e12
+
+    out = {
+        "metric": METRIC, "value": round(value, 2), "unit": "TFLOP/s", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(wall * 1e3, 5),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16",
+        "data": "synthetic",
+        "config": {"workload": "bf16-in/fp32-acc/bf16-out GEMM M=N=K=4096 row-major (NN) beta=0, N(0,1) inputs",
+                   "variant": variant, "split": split},
+        "roofline": {"bound": "mfma", "achieved": round(achieved, 2), "peak": PEAK_BF16, "unit": "TFLOP/s",
+                     "frac": round(achieved / PEAK_BF16, 4), "traffic": None,
+                     "kernel": variant, "us_per_launch": round(ev * 1e6, 2)},
+    }
+
+    # ------------------------------------------------------------------ CPU oracle beside it (bounded sample)
+    if not args.no_cpu:
+        from oracle import reference as oracle
+        rows_probe = list(range(0, M, M // 64))[:64]
+        t0 = time.perf_counter()
+        oracle.gemm_ref(case.A, K, case.B, N, M, N, K, rows=rows_probe)
+        rate = len(rows_probe) * N * K / (time.perf_counter() - t0)          # MAC/s
+        n_rows = int(min(M, max(128, 12.0 * rate / (N * K))))
+        rows = sorted(set(np.linspace(0, M - 1, n_rows).astype(int).tolist()))
+        t0 = time.perf_counter()
+        ref = oracle.gemm_ref(case.A, K, case.B, N, M, N, K, rows=rows)
+        dt = time.perf_counter() - t0
+        got = oracle.bf16_to_f64(dC.cpu().numpy().view(np.uint16)[rows])
+        err = float(np.linalg.norm(got - ref) / np.linalg.norm(ref))
+        out["cpu_baseline"] = {"value": round(2.0 * len(rows) * N * K / dt / 1e12, 5), "unit": "TFLOP/s",
+                               "cores": oracle.num_threads(), "kind": "oracle",
+                               "sample": f"{len(rows)} of {M} complete rows of C of the same 4096^3 problem "
+                                         f"({dt:.1f} s); GPU rows match them to rel. Frobenius {err:.2e}"}
+        assert err <= 2e-3, f"GPU result disagrees with the oracle: {err}"
+
+    # ------------------------------------------------------------------ the other configurations
+    if not args.no_others:
+        others = {}
+
+        def record(name, flops_, fn, peak, steps=50, warmup=5, bytes_=None):
+            w_, e_ = time_launches(fn, steps, warmup)
+            r = {"us": round(e_ * 1e6, 2), "tflops": round(flops_ / e_ / 1e12, 2),
+                 "frac_mfma_peak": round(flops_ / e_ / 1e12 / peak, 4),
+                 "variant": B.gemm_variant_name(B.gemm_last_variant()), "split": B.gemm_last_split()}
+            if bytes_ is not None:
+                r["hbm_gbs"] = round(bytes_ / e_ / 1e9, 1)
+                r["frac_hbm_peak"] = round(bytes_ / e_ / 1e12 / HBM_TBS, 4)
+            others[name] = r
+
+        # fp32 2048^3 with beta = 0.5
+        c2 = W.config2_f32_2048()
+        a2, b2, c2d = dev(c2.A), dev(c2.B), dev(c2.C0.copy())
+        record("f32_2048_beta0.5", c2.flops,
+               lambda: B.gemm_f32(0, 0, 2048, 2048, 2048, a2, 2048, b2, 2048, 0.5, c2d, 2048, workspace=ws), PEAK_F32)
+        del a2, b2, c2d
+        # bf16 squares (random device data of the same distribution: timing only)
+        for s in (1024, 2048, 8192):
+            a = torch.randn((s, s), device="cuda").to(torch.bfloat16)
+            b = torch.randn((s, s), device="cuda").to(torch.bfloat16)
+            c = torch.empty((s, s), device="cuda", dtype=torch.bfloat16)
+            record(f"bf16_{s}", 2.0 * s ** 3,
+                   lambda: B.gemm_bf16(0, 0, s, s, s, a, s, b, s, 0.0, c, s, 0, workspace=ws), PEAK_BF16,
+                   steps=20 if s == 8192 else 100)
+            del a, b, c
+        # MLP shapes, weights stored N x K
+        for which, (Kk, Nn) in (("up", (4096, 11008)), ("down", (11008, 4096))):
+            wgt = (torch.randn((Nn, Kk), device="cuda") * 0.02).to(torch.bfloat16)
+            for Mm in (4096, 128, 16):
+                a = torch.randn((Mm, Kk), device="cuda").to(torch.bfloat16)
+                c = torch.empty((Mm, Nn), device="cuda", dtype=torch.bfloat16)
+                bytes_ = 2.0 * (Mm * Kk + Kk * Nn + Mm * Nn)
+                record(f"mlp_{which}_M{Mm}", 2.0 * Mm * Nn * Kk,
+                       lambda: B.gemm_bf16(0, 1, Mm, Nn, Kk, a, Kk, wgt, Kk, 0.0, c, Nn, 0, workspace=ws),
+                       PEAK_BF16, steps=30 if Mm == 4096 else 100, bytes_=bytes_ if Mm <= 128 else None)
+                del a, c
+            del wgt
+        # batch-reduce over scattered tiles
+        c5 = W.config5_brgemm()
+        pool = dev(c5.pool)
+        ao, bo = torch.from_numpy(c5.A_off).cuda(), torch.from_numpy(c5.B_off).cuda()
+        cc = torch.zeros((c5.M, c5.N), dtype=torch.float32, device="cuda")
+        record("brgemm_512x512x64x64", c5.flops,
+               lambda: B.brgemm_bf16(0, 0, c5.M, c5.N, c5.K, c5.batch, pool, ao, c5.lda, pool, bo, c5.ldb, 1.0,
+                                     cc, c5.N, workspace=ws), PEAK_BF16, steps=200, warmup=20)
+        out["others"] = others
+
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()
