@@ -18,238 +18,16 @@
 // order, so the swizzle that keeps the LDS reads bank-conflict free is applied by
 // choosing WHICH 16 global bytes each lane fetches.  Two LDS stages; the block
 // for k-step t+2 is requested while block t's last slice is being multiplied.
-#include "common.hpp"
-#include "variants.hpp"
-#include <type_traits>
+#include "bf16_tiles.hpp"
 
 namespace brg {
-
-typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
-typedef __attribute__((ext_vector_type(16))) float f32x16;
-typedef __attribute__((ext_vector_type(4))) float f32x4;
-typedef __attribute__((ext_vector_type(4))) short s16x4;
-typedef __attribute__((ext_vector_type(8))) short s16x8;
-
-#define LDS_AS __attribute__((address_space(3)))
-#define GLB_AS __attribute__((address_space(1)))
-
-constexpr int BK = 64;                  // k-block depth (elements) = 128 bytes of bf16
-
-struct Bf16Args {
-    int64_t M, N, K, batch;
-    const uint16_t *A;
-    const int64_t *A_off;
-    int64_t lda;
-    const uint16_t *B;
-    const int64_t *B_off;
-    int64_t ldb;
-    Epilogue epi;
-    int split;
-    float *partial;
-    int tiles_m, tiles_n;
-};
-
-// s_waitcnt immediates for gfx9-family encodings: vmcnt in bits [3:0] and [15:14],
-// expcnt [6:4], lgkmcnt [11:8].
-__device__ __forceinline__ void wait_vmcnt0() { __builtin_amdgcn_s_waitcnt(0x0F70); }
-__device__ __forceinline__ void wait_lgkmcnt0() { __builtin_amdgcn_s_waitcnt(0xC07F); }
-
-__device__ __forceinline__ void load16_to_lds(const uint16_t *g, uint32_t lds_byte, LDS_AS char *lds0)
-{
-    __builtin_amdgcn_global_load_lds((const GLB_AS void *)g, (LDS_AS void *)(lds0 + lds_byte), 16, 0, 0);
-}
-
-// ---------------------------------------------------------------------------
-// Operand tile whose contiguous direction is k ("K-major": A with transA == 0,
-// B with transB == 1).  LDS image: row r (an m or n index) takes 128 bytes; its
-// 16-byte chunk c (8 consecutive k) sits at chunk position c ^ (r & 7).
-// ---------------------------------------------------------------------------
-template <int ROWS>
-struct KMajorTile {
-    static constexpr int kInstr = ROWS / 8;          // wave-instructions per tile
-    static constexpr int kPerWave = kInstr / 4;
-
-    // Global element offset (relative to the tile's k-block origin) this lane fetches
-    // for wave-instruction j of wave w.  row_limit clamps ragged edges to a valid row.
-    __device__ static int64_t src_offset(int w, int j, int lane, int64_t row0, int64_t row_limit, int64_t ld)
-    {
-        const int g = w * kPerWave + j;
-        int64_t row = row0 + 8 * g + (lane >> 3);
-        row = row < row_limit ? row : row_limit - 1;
-        const int c = (lane & 7) ^ (lane >> 3);
-        return row * ld + 8 * c;
-    }
-    __device__ static uint32_t dst_byte(int w, int j) { return (uint32_t)(w * kPerWave + j) * 1024u; }
-
-    // Byte offset of the 8 k-values lane `lane` needs for MFMA tile `t` (32 rows) and
-    // k-slice ks (16 k): row t*32 + lane%32, chunk 2*ks + lane/32.
-    __device__ static uint32_t frag_byte(int row_base, int t, int ks, int lane)
-    {
-        const int r = row_base + t * 32 + (lane & 31);
-        const int c = 2 * ks + (lane >> 5);
-        return (uint32_t)(r * 128 + ((c ^ (r & 7)) << 4));
-    }
-    __device__ static bf16x8 read_frag(LDS_AS char *tile, int row_base, int t, int ks, int lane)
-    {
-        return *(LDS_AS bf16x8 *)(tile + frag_byte(row_base, t, ks, lane));
-    }
-};
-
-// ---------------------------------------------------------------------------
-// Operand tile whose contiguous direction is m or n ("MN-major": A with
-// transA == 1, B with transB == 0).  LDS image: k-row kr takes COLS*2 bytes; its
-// 16-byte chunk c (8 consecutive m/n) sits at chunk position c ^ ((kr & 3) << 2),
-// which spreads the four k-rows one transposing read touches over distinct banks.
-// ---------------------------------------------------------------------------
-template <int COLS>
-struct MNMajorTile {
-    static constexpr int kChunksPerRow = COLS / 8;
-    static constexpr int kRowBytes = COLS * 2;
-    static constexpr int kInstr = BK * kChunksPerRow / 64;
-    static constexpr int kPerWave = kInstr / 4;
-
-    __device__ static int64_t src_offset(int w, int j, int lane, int64_t col0, int64_t col_limit, int64_t ld)
-    {
-        const int idx = (w * kPerWave + j) * 64 + lane;
-        const int kr = idx / kChunksPerRow;
-        const int pc = idx % kChunksPerRow;
-        const int c = pc ^ ((kr & 3) << 2);
-        int64_t col = col0 + 8 * c;
-        col = col < col_limit ? col : col0;           // chunk wholly outside: any valid chunk
-        return (int64_t)kr * ld + col;
-    }
-    __device__ static uint32_t dst_byte(int w, int j) { return (uint32_t)(w * kPerWave + j) * 1024u; }
-
-    // ds_read_b64_tr_b16 works on blocks of 16 lanes: lane i of a block supplies the
-    // address of 4 consecutive columns (4*(i%4)..) of k-row (i/4) and receives, for
-    // column i, the 4 k-values of those rows.  Two reads give the 8 k-values of the
-    // MFMA operand: k = 8*(lane/32) + 4*rd + 0..3 within the 16-deep slice.
-    __device__ static bf16x8 read_frag(LDS_AS char *tile, int col_base, int t, int ks, int lane)
-    {
-        const int b = lane >> 4, i = lane & 15;
-        const int col = col_base + t * 32 + 16 * (b & 1) + 4 * (i & 3);
-        const int c = col >> 3;
-        const int within = (col & 7) * 2;
-        s16x4 v[2];
-#pragma unroll
-        for (int rd = 0; rd < 2; ++rd) {
-            const int kr = ks * 16 + 8 * (b >> 1) + 4 * rd + (i >> 2);
-            const uint32_t byte = (uint32_t)(kr * kRowBytes + ((c ^ ((kr & 3) << 2)) << 4) + within);
-            v[rd] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((LDS_AS s16x4 *)(tile + byte));
-        }
-        s16x8 r = __builtin_shufflevector(v[0], v[1], 0, 1, 2, 3, 4, 5, 6, 7);
-        return __builtin_bit_cast(bf16x8, r);
-    }
-};
-
-template <int EXTENT, bool KMAJ>
-struct TileOf;
-template <int EXTENT>
-struct TileOf<EXTENT, true> { typedef KMajorTile<EXTENT> type; };
-template <int EXTENT>
-struct TileOf<EXTENT, false> { typedef MNMajorTile<EXTENT> type; };
-
-// XCD-aware tile order.  Workgroups are dealt round-robin to the 8 XCDs (each with
-// its own L2), so workgroup w is renumbered to t = (w % 8) * (T/8) + w / 8: every
-// XCD then owns a contiguous run of logical tiles, and logical tiles are walked in
-// groups of GM tile-rows so that a run shares few A row-panels and B column-panels.
-__device__ __forceinline__ void tile_coords(int w, int tiles_m, int tiles_n, int &tm, int &tn)
-{
-    const int T = tiles_m * tiles_n;
-    const int T8 = T & ~7;
-    int t = w;
-    if (w < T8)
-        t = (w & 7) * (T8 >> 3) + (w >> 3);
-    constexpr int GM = 4;
-    const int per_group = GM * tiles_n;
-    const int group = t / per_group;
-    const int first_m = group * GM;
-    const int gsize = (tiles_m - first_m) < GM ? (tiles_m - first_m) : GM;
-    const int in_group = t - group * per_group;
-    tm = first_m + in_group % gsize;
-    tn = in_group / gsize;
-}
-
-template <int I, int N, typename F>
-__device__ __forceinline__ void static_for(F &&f)
-{
-    if constexpr (I < N) {
-        f(std::integral_constant<int, I>{});
-        static_for<I + 1, N>(f);
-    }
-}
-
-// Four consecutive columns n..n+3 of row m, values already final sums.  `left` is
-// N - n (columns that exist); `vec` says 16-byte (fp32) / 8-byte (bf16) accesses
-// are aligned.
-__device__ __forceinline__ void store4_partial(float *dst, int64_t left, bool vec, float v0, float v1, float v2,
-                                               float v3)
-{
-    if (left <= 0)
-        return;
-    if (vec && left >= 4) {
-        *(f32x4 *)dst = f32x4{v0, v1, v2, v3};
-    } else {
-        dst[0] = v0;
-        if (left > 1) dst[1] = v1;
-        if (left > 2) dst[2] = v2;
-        if (left > 3) dst[3] = v3;
-    }
-}
-
-__device__ __forceinline__ void store4_epilogue(const Epilogue &e, int64_t m, int64_t n, int64_t left, bool vec,
-                                                float v0, float v1, float v2, float v3)
-{
-    if (left <= 0)
-        return;
-    if (!(vec && left >= 4)) {
-        epilogue_store(e, v0, m, n);
-        if (left > 1) epilogue_store(e, v1, m, n + 1);
-        if (left > 2) epilogue_store(e, v2, m, n + 2);
-        if (left > 3) epilogue_store(e, v3, m, n + 3);
-        return;
-    }
-    if (e.beta != 0.0f) {
-        if (e.c_f32) {
-            const f32x4 old = *(const f32x4 *)((const float *)e.C + m * e.ldc + n);
-            v0 = fmaf(e.beta, old[0], v0);
-            v1 = fmaf(e.beta, old[1], v1);
-            v2 = fmaf(e.beta, old[2], v2);
-            v3 = fmaf(e.beta, old[3], v3);
-        } else {
-            const uint2 old = *(const uint2 *)((const uint16_t *)e.C + m * e.ldc + n);
-            v0 = fmaf(e.beta, __uint_as_float(old.x << 16), v0);
-            v1 = fmaf(e.beta, __uint_as_float(old.x & 0xffff0000u), v1);
-            v2 = fmaf(e.beta, __uint_as_float(old.y << 16), v2);
-            v3 = fmaf(e.beta, __uint_as_float(old.y & 0xffff0000u), v3);
-        }
-    }
-    if (e.bias) {
-        const f32x4 bv = *(const f32x4 *)(e.bias + n);     // n is a multiple of 4; bias from hipMalloc
-        v0 += bv[0]; v1 += bv[1]; v2 += bv[2]; v3 += bv[3];
-    }
-    if (e.relu) {
-        v0 = v0 < 0.0f ? 0.0f : v0;
-        v1 = v1 < 0.0f ? 0.0f : v1;
-        v2 = v2 < 0.0f ? 0.0f : v2;
-        v3 = v3 < 0.0f ? 0.0f : v3;
-    }
-    if (e.c_f32) {
-        *(f32x4 *)((float *)e.C + m * e.ldc + n) = f32x4{v0, v1, v2, v3};
-    } else {
-        uint2 out;
-        out.x = (uint32_t)f32_to_bf16_rne(v0) | ((uint32_t)f32_to_bf16_rne(v1) << 16);
-        out.y = (uint32_t)f32_to_bf16_rne(v2) | ((uint32_t)f32_to_bf16_rne(v3) << 16);
-        *(uint2 *)((uint16_t *)e.C + m * e.ldc + n) = out;
-    }
-}
 
 template <int BM, int BN, bool A_KMAJ, bool B_KMAJ>
 __global__ void __launch_bounds__(256)
 bf16_mfma_kernel(Bf16Args p)
 {
-    typedef typename TileOf<BM, A_KMAJ>::type ATile;
-    typedef typename TileOf<BN, B_KMAJ>::type BTile;
+    typedef typename TileOf<BM, 4, A_KMAJ>::type ATile;
+    typedef typename TileOf<BN, 4, B_KMAJ>::type BTile;
     constexpr int WM = BM / 2, WN = BN / 2;         // wave tile
     constexpr int TM = WM / 32, TN = WN / 32;       // MFMA tiles per wave tile
     constexpr uint32_t A_BYTES = BM * BK * 2, B_BYTES = BN * BK * 2;

@@ -1,0 +1,322 @@
+// bf16 BRGEMM kernel for gfx950 with two wavefronts per SIMD working in
+// alternating phases ("ping-pong"): 256 x 256 x 64 workgroup tile, 8 wavefronts,
+// each keeping a 128 x 64 accumulator tile in registers for the whole batch and K
+// loops (Section 2.1 advantage (1); Section 3.1: the register tile is sized so that
+// accumulators, the operand fragments of one phase and the load addresses fit the
+// 256 registers a lane has at this occupancy, with no spills).
+//
+// Why two waves per SIMD: a global->LDS load holds the issuing wave until the
+// address unit has taken it (about 15 cycles per 1 KiB wave-load per CU, i.e. the
+// 64 B/clk of the vector memory path), and the 64 loads a k-block needs occupy
+// that unit for about half of the block's MFMA time.  With one wave per SIMD that
+// time is lost to the matrix pipe; here one wave of each SIMD issues loads and LDS
+// fragment reads ("memory phase") while the other issues nothing but its 32 MFMAs
+// ("compute phase"), and a workgroup barrier swaps the roles.  Waves 4-7 run the
+// same sequence one phase behind waves 0-3.  It is the software pipelining of
+// operand re-layout against the matrix instruction that the paper applies to its
+// flat-layout AMX kernels (Section 4.3), done across waves.
+//
+// LDS holds five 32 KiB slots used as a ring of half-blocks A(0) B(0) A(1) B(1) ...
+// With five slots the A half of block t+2 has a free slot while block t is still
+// being read, so every load is requested at least one and a half phases (~1500
+// cycles) before the barrier that publishes it: waves 0-3 request B(t+1) in their
+// memory phase of block t, waves 4-7 request A(t+2) in theirs.
+#include "bf16_tiles.hpp"
+
+namespace brg {
+
+namespace {
+
+constexpr int PP_BM = 256, PP_BN = 256, PP_NW = 8;
+constexpr int PP_WM = 128, PP_WN = 64;          // wave tile
+constexpr int PP_TM = PP_WM / 32, PP_TN = PP_WN / 32;
+constexpr uint32_t PP_A_BYTES = PP_BM * BK * 2, PP_B_BYTES = PP_BN * BK * 2;
+constexpr uint32_t PP_SLOT = 32768;              // one half-block (A or B part of a k-block)
+constexpr int PP_SLOTS = 5;
+static_assert(PP_A_BYTES == PP_SLOT && PP_B_BYTES == PP_SLOT, "half-blocks are one slot each");
+constexpr int PP_EPI_LD = PP_WN + 4;            // floats per staged epilogue row (272 B: conflict-free)
+
+__device__ __forceinline__ void phase_sync()
+{
+    __builtin_amdgcn_sched_barrier(0);
+    asm volatile("" ::: "memory");
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
+    __builtin_amdgcn_sched_barrier(0);
+}
+
+}  // namespace
+
+template <bool A_KMAJ, bool B_KMAJ>
+__global__ void __launch_bounds__(512)
+bf16_pingpong_kernel(Bf16Args p)
+{
+    // Load duty: waves 0-3 fetch the B halves, waves 4-7 the A halves (8 wave-loads
+    // per half-block each), so the tile classes are instantiated for 4 loader waves.
+    typedef typename TileOf<PP_BM, 4, A_KMAJ>::type ATile;
+    typedef typename TileOf<PP_BN, 4, B_KMAJ>::type BTile;
+    static_assert(ATile::kPerWave == 8 && BTile::kPerWave == 8, "8 wave-loads per loader wave");
+
+    extern __shared__ __attribute__((aligned(1024))) char smem_generic[];
+    LDS_AS char *smem = (LDS_AS char *)smem_generic;
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wm = w & 1, wn = (w >> 1) & 3;
+    const int group = w >> 2;                   // waves w and w+4 share a SIMD
+    const int wl = w & 3;                       // index among the loaders of one operand
+
+    int tm, tn;
+    tile_coords(blockIdx.x, p.tiles_m, p.tiles_n, tm, tn);
+    const int64_t m0 = (int64_t)tm * PP_BM, n0 = (int64_t)tn * PP_BN;
+
+    const int kblocks = (int)(p.K / BK);
+    const int total = (int)p.batch * kblocks;
+    const int per = (total + p.split - 1) / p.split;
+    const int it_begin = (int)blockIdx.y * per;
+    const int it_end = (it_begin + per < total) ? it_begin + per : total;
+    const int n_iter = it_end - it_begin;
+
+    // This wave's operand (A for waves 4-7, B for waves 0-3).  Wave-load g = 8*wl + j of
+    // a half-block is addressed as scalar base + g * stride + a 32-bit lane offset that
+    // only depends on the parity of g (two registers for the whole kernel).
+    const uint16_t *op_base = group ? p.A : p.B;
+    const int64_t *op_off = group ? p.A_off : p.B_off;
+    const int64_t op_ld = group ? p.lda : p.ldb;
+    const int64_t op_first = group ? m0 : n0;             // first row / column of the tile
+    const int64_t op_limit = group ? p.M : p.N;
+    const int64_t op_origin = group ? (A_KMAJ ? m0 * p.lda : m0) : (B_KMAJ ? n0 * p.ldb : n0);
+    const int64_t op_kstep = group ? (A_KMAJ ? (int64_t)BK : (int64_t)BK * p.lda)
+                                   : (B_KMAJ ? (int64_t)BK : (int64_t)BK * p.ldb);
+    const uint32_t lane_off0 = group ? ATile::lane_off_bytes(0, lane, op_ld) : BTile::lane_off_bytes(0, lane, op_ld);
+    const uint32_t lane_off1 = group ? ATile::lane_off_bytes(1, lane, op_ld) : BTile::lane_off_bytes(1, lane, op_ld);
+    const int64_t g_stride = group ? ATile::instr_stride_bytes(op_ld) : BTile::instr_stride_bytes(op_ld);
+    // Only a tile on the ragged edge of the matrix needs lanes switched off.
+    const bool edge = op_first + (group ? PP_BM : PP_BN) > op_limit;
+
+    // Tile offsets live in device memory; a misaligned one sends the whole workgroup
+    // to the register-staged loader (2-byte loads).
+    // (The vote goes through the dynamic LDS: all 160 KiB are claimed by the slots,
+    // so nothing here may use static LDS.)
+    bool direct = true;
+    if (p.A_off) {
+        int bad = 0;
+        for (int i = tid; i < (int)p.batch; i += 512)
+            bad |= (((p.A_off[i] | p.B_off[i]) & 7) != 0);
+        const bool wave_bad = __builtin_amdgcn_ballot_w64(bad != 0) != 0;
+        LDS_AS int *vote = (LDS_AS int *)smem;
+        if (lane == 0)
+            vote[w] = wave_bad ? 1 : 0;
+        __syncthreads();
+        int any_bad = 0;
+#pragma unroll
+        for (int i = 0; i < PP_NW; ++i)
+            any_bad |= vote[i];
+        direct = any_bad == 0;
+        __syncthreads();
+    }
+
+    // Load cursor of this wave's operand: next block's (batch index, k-block), its
+    // source pointer and its ring slot.  Half-block 2t is A(t), 2t+1 is B(t); slot = index % 5.
+    int ld_i = n_iter > 0 ? it_begin / kblocks : 0;
+    int ld_kb = n_iter > 0 ? it_begin - ld_i * kblocks : 0;
+    const uint16_t *ld_ptr = uniform_ptr(op_base + (op_off ? op_off[ld_i] : 0) + op_origin + ld_kb * op_kstep);
+    int ld_slot = group ? 0 : 1;
+
+    auto issue_half = [&]() {
+        const uint32_t base = (uint32_t)ld_slot * PP_SLOT;
+        const char *g = (const char *)ld_ptr;
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            const int gi = wl * 8 + j;
+            const char *gj = g + (int64_t)gi * g_stride;
+            const uint32_t off = (j & 1) ? lane_off1 : lane_off0;
+            const uint32_t dst = base + (uint32_t)gi * 1024u;
+            const bool on = !edge || (group ? ATile::lane_valid(gi, lane, op_first, op_limit)
+                                            : BTile::lane_valid(gi, lane, op_first, op_limit));
+            if (on) {
+                if (direct) {
+                    load16_to_lds_saddr(gj, off, (uint32_t)(size_t)(smem + dst));
+                } else {
+                    const uint16_t *h = (const uint16_t *)(gj + off);
+                    s16x8 v;
+#pragma unroll
+                    for (int e = 0; e < 8; ++e)
+                        v[e] = (short)h[e];
+                    *(LDS_AS s16x8 *)(smem + dst + lane * 16) = v;
+                }
+            }
+        }
+        ld_slot = ld_slot + 2 >= PP_SLOTS ? ld_slot + 2 - PP_SLOTS : ld_slot + 2;
+        if (++ld_kb == kblocks) {
+            ld_kb = 0;
+            ++ld_i;
+            if (op_off && ld_i < (int)p.batch)
+                ld_ptr = uniform_ptr(op_base + op_off[ld_i] + op_origin);
+        } else {
+            ld_ptr += op_kstep;
+        }
+    };
+
+    f32x16 acc[PP_TN][PP_TM];
+#pragma unroll
+    for (int a = 0; a < PP_TN; ++a)
+#pragma unroll
+        for (int b = 0; b < PP_TM; ++b)
+#pragma unroll
+            for (int r = 0; r < 16; ++r)
+                acc[a][b][r] = 0.0f;
+
+    // Memory phase: every fragment of one k-block (4 slices of 16) into registers.
+    bf16x8 fa[4][PP_TM], fb[4][PP_TN];
+    int rd_slot = 0;                            // slot of A(t); B(t) is the next one
+    auto read_block = [&]() {
+        LDS_AS char *at = smem + (uint32_t)rd_slot * PP_SLOT;
+        LDS_AS char *bt = smem + (uint32_t)(rd_slot + 1 == PP_SLOTS ? 0 : rd_slot + 1) * PP_SLOT;
+#pragma unroll
+        for (int s = 0; s < 4; ++s) {
+#pragma unroll
+            for (int t = 0; t < PP_TM; ++t)
+                fa[s][t] = ATile::read_frag(at, wm * PP_WM, t, s, lane);
+#pragma unroll
+            for (int t = 0; t < PP_TN; ++t)
+                fb[s][t] = BTile::read_frag(bt, wn * PP_WN, t, s, lane);
+        }
+        rd_slot = rd_slot + 2 >= PP_SLOTS ? rd_slot + 2 - PP_SLOTS : rd_slot + 2;
+    };
+    // Compute phase: 32 MFMAs.  Operands are passed swapped (B fragment first) so the
+    // 32x32 result is C^T: lane l owns row m = l%32 and 4 consecutive columns per
+    // group of 4 registers.
+    auto compute_block = [&]() {
+#pragma unroll
+        for (int s = 0; s < 4; ++s)
+#pragma unroll
+            for (int a = 0; a < PP_TN; ++a)
+#pragma unroll
+                for (int b = 0; b < PP_TM; ++b)
+                    acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[s][a], fa[s][b], acc[a][b], 0, 0, 0);
+    };
+
+    if (n_iter > 0) {
+        // Prologue: A(0), A(1) by waves 4-7, B(0) by waves 0-3.
+        issue_half();
+        if (group == 1 && n_iter > 1)
+            issue_half();
+        wait_vmcnt0();
+        wait_lgkmcnt0();
+        phase_sync();
+        if (group == 1)
+            phase_sync();                       // waves 4-7 run one phase behind
+
+        for (int t = 0; t < n_iter; ++t) {
+            // ---- memory phase.  Waves 0-3 request B(t+1): its slot held A(t-1), last
+            // read one phase ago.  Waves 4-7 request A(t+2): its slot held B(t-1).
+            // The fragment reads go first: LDS reads issued behind global->LDS loads of
+            // the same wave do not complete until those loads have landed.
+            const bool request = group == 0 ? (t + 1 < n_iter) : (t + 2 < n_iter);
+            read_block();
+            wait_lgkmcnt0();
+            __builtin_amdgcn_sched_barrier(0);
+            if (request)
+                issue_half();
+            if (group == 1) {
+                // A(t+1), requested one block ago, must have landed before the barrier
+                // that precedes its first read; the 8 loads just issued may still fly.
+                if (request)
+                    wait_vmcnt8();
+                else
+                    wait_vmcnt0();
+            }
+            phase_sync();
+            // ---- compute phase
+            compute_block();
+            __builtin_amdgcn_sched_barrier(0);  // keep the wait behind the MFMAs
+            if (group == 0)
+                wait_vmcnt0();                  // B(t+1) has landed (requested a phase ago)
+            phase_sync();
+        }
+        if (group == 0)
+            phase_sync();
+    }
+
+    // ---- epilogue.  Each wave stages 32 rows x 64 columns of its tile at a time in
+    // its own 8.5 KiB of LDS (all stages are free now), reads them back row-wise and
+    // stores 4 rows x 64 columns per instruction: full cache lines for both output types.
+    LDS_AS float *stage_f = (LDS_AS float *)(smem + (uint32_t)w * (32 * PP_EPI_LD * 4));
+    const bool to_partial = p.split > 1;
+    float *part = to_partial ? p.partial + (int64_t)blockIdx.y * p.M * p.N : nullptr;
+    const bool vec = to_partial ? ((p.N & 3) == 0)
+                                : ((p.epi.ldc & 3) == 0 && (((uintptr_t)p.epi.C) & 15) == 0);
+    static_for<0, PP_TM>([&](auto bc) {
+        constexpr int b = decltype(bc)::value;
+        asm volatile("" ::: "memory");
+        static_for<0, PP_TN * 4>([&](auto aq) {
+            constexpr int a = decltype(aq)::value / 4, q = decltype(aq)::value % 4;
+            const int col = a * 32 + 8 * q + 4 * (lane >> 5);
+            *(LDS_AS f32x4 *)(stage_f + (lane & 31) * PP_EPI_LD + col) =
+                f32x4{acc[a][b][4 * q + 0], acc[a][b][4 * q + 1], acc[a][b][4 * q + 2], acc[a][b][4 * q + 3]};
+        });
+        asm volatile("" ::: "memory");
+        __builtin_amdgcn_wave_barrier();
+#pragma unroll 2
+        for (int i = 0; i < 8; ++i) {
+            const int idx = i * 64 + lane;
+            const int row = idx >> 4, c4 = idx & 15;
+            const f32x4 v = *(LDS_AS f32x4 *)(stage_f + row * PP_EPI_LD + c4 * 4);
+            const int64_t m = m0 + wm * PP_WM + b * 32 + row;
+            const int64_t n = n0 + wn * PP_WN + c4 * 4;
+            if (m < p.M) {
+                if (to_partial)
+                    store4_partial(part + m * p.N + n, p.N - n, vec, v[0], v[1], v[2], v[3]);
+                else
+                    store4_epilogue(p.epi, m, n, p.N - n, vec, v[0], v[1], v[2], v[3]);
+            }
+        }
+        __builtin_amdgcn_wave_barrier();
+    });
+}
+
+static hipError_t launch_pp(const Problem &p)
+{
+    Bf16Args a;
+    a.M = p.M; a.N = p.N; a.K = p.K; a.batch = p.batch;
+    a.A = (const uint16_t *)p.A; a.A_off = p.A_off; a.lda = p.lda;
+    a.B = (const uint16_t *)p.B; a.B_off = p.B_off; a.ldb = p.ldb;
+    a.epi.beta = p.beta; a.epi.C = p.C; a.epi.ldc = p.ldc; a.epi.c_f32 = p.c_f32;
+    a.epi.bias = p.bias; a.epi.relu = p.relu;
+    a.split = p.split; a.partial = p.partial;
+    a.tiles_m = (int)((p.M + PP_BM - 1) / PP_BM);
+    a.tiles_n = (int)((p.N + PP_BN - 1) / PP_BN);
+    const dim3 grid((unsigned)(a.tiles_m * a.tiles_n), (unsigned)p.split);
+    const size_t lds = (size_t)PP_SLOTS * PP_SLOT;
+    const bool ak = p.transA == 0, bk = p.transB == 1;
+    void (*kern)(Bf16Args) = nullptr;
+    if (ak && bk) kern = bf16_pingpong_kernel<true, true>;
+    else if (ak && !bk) kern = bf16_pingpong_kernel<true, false>;
+    else if (!ak && bk) kern = bf16_pingpong_kernel<false, true>;
+    else kern = bf16_pingpong_kernel<false, false>;
+    static thread_local const void *configured[4] = {nullptr};
+    bool done = false;
+    for (const void *c : configured)
+        done = done || c == (const void *)kern;
+    if (!done) {
+        hipError_t e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e != hipSuccess)
+            return e;
+        for (auto &c : configured)
+            if (!c) { c = (const void *)kern; break; }
+    }
+    hipLaunchKernelGGL(kern, grid, dim3(512), lds, p.stream, a);
+    return hipGetLastError();
+}
+
+hipError_t launch_bf16_pingpong(const Problem &p) { return launch_pp(p); }
+
+// Same alignment rules as the 4-wave kernels, plus 32-bit lane offsets.
+bool bf16_pingpong_eligible(const Problem &p)
+{
+    return bf16_mfma_eligible(p) && p.lda < (1 << 22) && p.ldb < (1 << 22);
+}
+
+}  // namespace brg

@@ -1,0 +1,313 @@
+// Building blocks shared by the tuned bf16 kernels: LDS tile images and their
+// swizzles, MFMA fragment reads, the XCD-aware tile order and the 4-column epilogue.
+#pragma once
+#include "common.hpp"
+#include "variants.hpp"
+#include <type_traits>
+
+namespace brg {
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(16))) float f32x16;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
+typedef __attribute__((ext_vector_type(4))) short s16x4;
+typedef __attribute__((ext_vector_type(8))) short s16x8;
+
+#define LDS_AS __attribute__((address_space(3)))
+#define GLB_AS __attribute__((address_space(1)))
+
+constexpr int BK = 64;                  // k-block depth (elements) = 128 bytes of bf16
+
+struct Bf16Args {
+    int64_t M, N, K, batch;
+    const uint16_t *A;
+    const int64_t *A_off;
+    int64_t lda;
+    const uint16_t *B;
+    const int64_t *B_off;
+    int64_t ldb;
+    Epilogue epi;
+    int split;
+    float *partial;
+    int tiles_m, tiles_n;
+};
+
+// s_waitcnt immediates for gfx9-family encodings: vmcnt in bits [3:0] and [15:14],
+// expcnt [6:4], lgkmcnt [11:8].
+__device__ __forceinline__ void wait_vmcnt0() { __builtin_amdgcn_s_waitcnt(0x0F70); }
+__device__ __forceinline__ void wait_lgkmcnt0() { __builtin_amdgcn_s_waitcnt(0xC07F); }
+__device__ __forceinline__ void wait_vmcnt8() { __builtin_amdgcn_s_waitcnt(0x0F78); }
+
+// Tell the compiler a pointer is wave-uniform (keeps it in SGPRs).
+__device__ __forceinline__ const uint16_t *uniform_ptr(const uint16_t *p)
+{
+    const uint64_t v = (uint64_t)p;
+    const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)v);
+    const uint32_t hi = __builtin_amdgcn_readfirstlane((uint32_t)(v >> 32));
+    return (const uint16_t *)(((uint64_t)hi << 32) | lo);
+}
+
+// The same load in its scalar-base form: a wave-uniform 64-bit base in SGPRs plus
+// a 32-bit per-lane byte offset.  With 64-bit per-lane addresses the load's
+// address read competes with the MFMAs of the other wave on the SIMD for register
+// file bandwidth and issue takes ~2.5x longer (measured); this form does not.
+// lds_addr is the wave-uniform LDS byte address (goes to M0).  Not tracked by the
+// compiler's wait-count insertion: callers wait on vmcnt themselves.
+__device__ __forceinline__ void load16_to_lds_saddr(const char *base, uint32_t lane_off, uint32_t lds_addr)
+{
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
+                 :
+                 : "s"(lds_addr), "v"(lane_off), "s"(base)
+                 : "memory", "m0");
+}
+
+__device__ __forceinline__ void load16_to_lds(const uint16_t *g, uint32_t lds_byte, LDS_AS char *lds0)
+{
+    __builtin_amdgcn_global_load_lds((const GLB_AS void *)g, (LDS_AS void *)(lds0 + lds_byte), 16, 0, 0);
+}
+
+// ---------------------------------------------------------------------------
+// Operand tile whose contiguous direction is k ("K-major": A with transA == 0,
+// B with transB == 1).  LDS image: row r (an m or n index) takes 128 bytes; its
+// 16-byte chunk c (8 consecutive k) sits at chunk position c ^ ((r >> 1) & 7).
+// The LDS has 64 banks of 4 bytes, so two rows share one 256-byte bank window and
+// the 16 rows a 128-bit read serves per clock must land on 16 different 16-byte
+// positions of it: rows of equal parity need 8 different XOR values, hence r >> 1.
+// ---------------------------------------------------------------------------
+template <int ROWS, int NW>
+struct KMajorTile {
+    static constexpr int kInstr = ROWS / 8;          // wave-instructions per tile
+    static constexpr int kPerWave = kInstr / NW;
+
+    // Global element offset (relative to the tile's k-block origin) this lane fetches
+    // for wave-instruction j of wave w.  row_limit clamps ragged edges to a valid row.
+    __device__ static int64_t src_offset(int w, int j, int lane, int64_t row0, int64_t row_limit, int64_t ld)
+    {
+        const int g = w * kPerWave + j;
+        int64_t row = row0 + 8 * g + (lane >> 3);
+        row = row < row_limit ? row : row_limit - 1;
+        const int c = (lane & 7) ^ (((8 * g + (lane >> 3)) >> 1) & 7);
+        return row * ld + 8 * c;
+    }
+    __device__ static uint32_t dst_byte(int w, int j) { return (uint32_t)(w * kPerWave + j) * 1024u; }
+    // The same source position as a 32-bit byte offset from the tile origin
+    // (row row0, first k of the block): lets the load use a uniform base + lane offset.
+    __device__ static uint32_t src_rel_bytes(int w, int j, int lane, int64_t row0, int64_t row_limit, int64_t ld)
+    {
+        const int g = w * kPerWave + j;
+        int64_t row = row0 + 8 * g + (lane >> 3);
+        row = row < row_limit ? row : row_limit - 1;
+        const int c = (lane & 7) ^ (((8 * g + (lane >> 3)) >> 1) & 7);
+        return (uint32_t)(((row - row0) * ld + 8 * c) * 2);
+    }
+
+    // Scalar-base form of the same addressing.  Wave-instruction g of the tile reads
+    // rows 8g..8g+7: a per-instruction scalar offset g * instr_stride_bytes(ld), plus a
+    // lane offset that depends on g only through its parity (the swizzle term 4*(g&1)).
+    // Lanes whose row lies outside the matrix are switched off instead of redirected.
+    __device__ static int64_t instr_stride_bytes(int64_t ld) { return 8 * ld * 2; }
+    __device__ static uint32_t lane_off_bytes(int parity, int lane, int64_t ld)
+    {
+        const int c = (lane & 7) ^ ((4 * parity + (lane >> 4)) & 7);
+        return (uint32_t)(((int64_t)(lane >> 3) * ld + 8 * c) * 2);
+    }
+    __device__ static bool lane_valid(int g, int lane, int64_t row0, int64_t row_limit)
+    {
+        return row0 + 8 * g + (lane >> 3) < row_limit;
+    }
+
+    // Byte offset of the 8 k-values lane `lane` needs for MFMA tile `t` (32 rows) and
+    // k-slice ks (16 k): row t*32 + lane%32, chunk 2*ks + lane/32.
+    __device__ static uint32_t frag_byte(int row_base, int t, int ks, int lane)
+    {
+        const int r = row_base + t * 32 + (lane & 31);
+        const int c = 2 * ks + (lane >> 5);
+        return (uint32_t)(r * 128 + ((c ^ ((r >> 1) & 7)) << 4));
+    }
+    __device__ static bf16x8 read_frag(LDS_AS char *tile, int row_base, int t, int ks, int lane)
+    {
+        return *(LDS_AS bf16x8 *)(tile + frag_byte(row_base, t, ks, lane));
+    }
+};
+
+// ---------------------------------------------------------------------------
+// Operand tile whose contiguous direction is m or n ("MN-major": A with
+// transA == 1, B with transB == 0).  LDS image: k-row kr takes COLS*2 bytes; its
+// 16-byte chunk c (8 consecutive m/n) sits at chunk position c ^ ((kr & 3) << 2),
+// which spreads the four k-rows one transposing read touches over distinct banks.
+// ---------------------------------------------------------------------------
+template <int COLS, int NW>
+struct MNMajorTile {
+    static constexpr int kChunksPerRow = COLS / 8;
+    static constexpr int kRowBytes = COLS * 2;
+    static constexpr int kInstr = BK * kChunksPerRow / 64;
+    static constexpr int kPerWave = kInstr / NW;
+
+    __device__ static int64_t src_offset(int w, int j, int lane, int64_t col0, int64_t col_limit, int64_t ld)
+    {
+        const int idx = (w * kPerWave + j) * 64 + lane;
+        const int kr = idx / kChunksPerRow;
+        const int pc = idx % kChunksPerRow;
+        const int c = pc ^ ((kr & 3) << 2);
+        int64_t col = col0 + 8 * c;
+        col = col < col_limit ? col : col0;           // chunk wholly outside: any valid chunk
+        return (int64_t)kr * ld + col;
+    }
+    __device__ static uint32_t dst_byte(int w, int j) { return (uint32_t)(w * kPerWave + j) * 1024u; }
+    __device__ static uint32_t src_rel_bytes(int w, int j, int lane, int64_t col0, int64_t col_limit, int64_t ld)
+    {
+        const int idx = (w * kPerWave + j) * 64 + lane;
+        const int kr = idx / kChunksPerRow;
+        const int pc = idx % kChunksPerRow;
+        const int c = pc ^ ((kr & 3) << 2);
+        const int64_t rel = (col0 + 8 * c < col_limit) ? 8 * c : 0;
+        return (uint32_t)(((int64_t)kr * ld + rel) * 2);
+    }
+
+    // Scalar-base form: wave-instruction g reads k-rows (64/kChunksPerRow)*g.. ; the
+    // swizzle term depends on g only through its parity when a row is 32 chunks wide.
+    static_assert(kChunksPerRow == 32 || kChunksPerRow == 16, "row of 256 or 128 elements");
+    __device__ static int64_t instr_stride_bytes(int64_t ld) { return (64 / kChunksPerRow) * ld * 2; }
+    __device__ static uint32_t lane_off_bytes(int parity, int lane, int64_t ld)
+    {
+        // rows per instruction: 2 (32 chunks/row) or 4 (16 chunks/row)
+        const int kr_in = lane / kChunksPerRow;
+        const int pc = lane % kChunksPerRow;
+        const int kr_low = kChunksPerRow == 32 ? ((2 * parity + kr_in) & 3) : (kr_in & 3);
+        const int c = pc ^ (kr_low << 2);
+        return (uint32_t)(((int64_t)kr_in * ld + 8 * c) * 2);
+    }
+    __device__ static bool lane_valid(int g, int lane, int64_t col0, int64_t col_limit)
+    {
+        const int kr_in = lane / kChunksPerRow;
+        const int pc = lane % kChunksPerRow;
+        const int kr_low = kChunksPerRow == 32 ? ((2 * (g & 1) + kr_in) & 3) : (kr_in & 3);
+        const int c = pc ^ (kr_low << 2);
+        return col0 + 8 * c < col_limit;
+    }
+
+    // ds_read_b64_tr_b16 works on blocks of 16 lanes: lane i of a block supplies the
+    // address of 4 consecutive columns (4*(i%4)..) of k-row (i/4) and receives, for
+    // column i, the 4 k-values of those rows.  Two reads give the 8 k-values of the
+    // MFMA operand: k = 8*(lane/32) + 4*rd + 0..3 within the 16-deep slice.
+    __device__ static bf16x8 read_frag(LDS_AS char *tile, int col_base, int t, int ks, int lane)
+    {
+        const int b = lane >> 4, i = lane & 15;
+        const int col = col_base + t * 32 + 16 * (b & 1) + 4 * (i & 3);
+        const int c = col >> 3;
+        const int within = (col & 7) * 2;
+        s16x4 v[2];
+#pragma unroll
+        for (int rd = 0; rd < 2; ++rd) {
+            const int kr = ks * 16 + 8 * (b >> 1) + 4 * rd + (i >> 2);
+            const uint32_t byte = (uint32_t)(kr * kRowBytes + ((c ^ ((kr & 3) << 2)) << 4) + within);
+            v[rd] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((LDS_AS s16x4 *)(tile + byte));
+        }
+        s16x8 r = __builtin_shufflevector(v[0], v[1], 0, 1, 2, 3, 4, 5, 6, 7);
+        return __builtin_bit_cast(bf16x8, r);
+    }
+};
+
+template <int EXTENT, int NW, bool KMAJ>
+struct TileOf;
+template <int EXTENT, int NW>
+struct TileOf<EXTENT, NW, true> { typedef KMajorTile<EXTENT, NW> type; };
+template <int EXTENT, int NW>
+struct TileOf<EXTENT, NW, false> { typedef MNMajorTile<EXTENT, NW> type; };
+
+// XCD-aware tile order.  Workgroups are dealt round-robin to the 8 XCDs (each with
+// its own L2), so workgroup w is renumbered to t = (w % 8) * (T/8) + w / 8: every
+// XCD then owns a contiguous run of logical tiles, and logical tiles are walked in
+// groups of GM tile-rows so that a run shares few A row-panels and B column-panels.
+__device__ __forceinline__ void tile_coords(int w, int tiles_m, int tiles_n, int &tm, int &tn)
+{
+    const int T = tiles_m * tiles_n;
+    const int T8 = T & ~7;
+    int t = w;
+    if (w < T8)
+        t = (w & 7) * (T8 >> 3) + (w >> 3);
+    constexpr int GM = 4;
+    const int per_group = GM * tiles_n;
+    const int group = t / per_group;
+    const int first_m = group * GM;
+    const int gsize = (tiles_m - first_m) < GM ? (tiles_m - first_m) : GM;
+    const int in_group = t - group * per_group;
+    tm = first_m + in_group % gsize;
+    tn = in_group / gsize;
+}
+
+template <int I, int N, typename F>
+__device__ __forceinline__ void static_for(F &&f)
+{
+    if constexpr (I < N) {
+        f(std::integral_constant<int, I>{});
+        static_for<I + 1, N>(f);
+    }
+}
+
+// Four consecutive columns n..n+3 of row m, values already final sums.  `left` is
+// N - n (columns that exist); `vec` says 16-byte (fp32) / 8-byte (bf16) accesses
+// are aligned.
+__device__ __forceinline__ void store4_partial(float *dst, int64_t left, bool vec, float v0, float v1, float v2,
+                                               float v3)
+{
+    if (left <= 0)
+        return;
+    if (vec && left >= 4) {
+        *(f32x4 *)dst = f32x4{v0, v1, v2, v3};
+    } else {
+        dst[0] = v0;
+        if (left > 1) dst[1] = v1;
+        if (left > 2) dst[2] = v2;
+        if (left > 3) dst[3] = v3;
+    }
+}
+
+__device__ __forceinline__ void store4_epilogue(const Epilogue &e, int64_t m, int64_t n, int64_t left, bool vec,
+                                                float v0, float v1, float v2, float v3)
+{
+    if (left <= 0)
+        return;
+    if (!(vec && left >= 4)) {
+        epilogue_store(e, v0, m, n);
+        if (left > 1) epilogue_store(e, v1, m, n + 1);
+        if (left > 2) epilogue_store(e, v2, m, n + 2);
+        if (left > 3) epilogue_store(e, v3, m, n + 3);
+        return;
+    }
+    if (e.beta != 0.0f) {
+        if (e.c_f32) {
+            const f32x4 old = *(const f32x4 *)((const float *)e.C + m * e.ldc + n);
+            v0 = fmaf(e.beta, old[0], v0);
+            v1 = fmaf(e.beta, old[1], v1);
+            v2 = fmaf(e.beta, old[2], v2);
+            v3 = fmaf(e.beta, old[3], v3);
+        } else {
+            const uint2 old = *(const uint2 *)((const uint16_t *)e.C + m * e.ldc + n);
+            v0 = fmaf(e.beta, __uint_as_float(old.x << 16), v0);
+            v1 = fmaf(e.beta, __uint_as_float(old.x & 0xffff0000u), v1);
+            v2 = fmaf(e.beta, __uint_as_float(old.y << 16), v2);
+            v3 = fmaf(e.beta, __uint_as_float(old.y & 0xffff0000u), v3);
+        }
+    }
+    if (e.bias) {
+        const f32x4 bv = *(const f32x4 *)(e.bias + n);     // n is a multiple of 4; bias from hipMalloc
+        v0 += bv[0]; v1 += bv[1]; v2 += bv[2]; v3 += bv[3];
+    }
+    if (e.relu) {
+        v0 = v0 < 0.0f ? 0.0f : v0;
+        v1 = v1 < 0.0f ? 0.0f : v1;
+        v2 = v2 < 0.0f ? 0.0f : v2;
+        v3 = v3 < 0.0f ? 0.0f : v3;
+    }
+    if (e.c_f32) {
+        *(f32x4 *)((float *)e.C + m * e.ldc + n) = f32x4{v0, v1, v2, v3};
+    } else {
+        uint2 out;
+        out.x = (uint32_t)f32_to_bf16_rne(v0) | ((uint32_t)f32_to_bf16_rne(v1) << 16);
+        out.y = (uint32_t)f32_to_bf16_rne(v2) | ((uint32_t)f32_to_bf16_rne(v3) << 16);
+        *(uint2 *)((uint16_t *)e.C + m * e.ldc + n) = out;
+    }
+}
+
+}  // namespace brg

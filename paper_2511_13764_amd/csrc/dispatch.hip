@@ -10,6 +10,7 @@ const char *variant_name(int v)
     case V_GENERIC: return "generic_64x64x16_f32mfma";
     case V_BF16_256x256: return "bf16_256x256x64";
     case V_BF16_128x128: return "bf16_128x128x64";
+    case V_BF16_PP256: return "bf16_pingpong_256x256x64";
     default: return "";
     }
 }
@@ -20,6 +21,7 @@ bool variant_eligible(int v, const Problem &p)
     case V_GENERIC: return true;
     case V_BF16_256x256:
     case V_BF16_128x128: return bf16_mfma_eligible(p);
+    case V_BF16_PP256: return bf16_pingpong_eligible(p);
     default: return false;
     }
 }
@@ -56,6 +58,7 @@ hipError_t launch_variant(int v, const Problem &p)
     case V_GENERIC: return launch_generic(p);
     case V_BF16_256x256: return launch_bf16_256x256(p);
     case V_BF16_128x128: return launch_bf16_128x128(p);
+    case V_BF16_PP256: return launch_bf16_pingpong(p);
     default: return hipErrorInvalidValue;
     }
 }
