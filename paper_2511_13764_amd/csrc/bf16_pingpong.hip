@@ -47,9 +47,12 @@ __device__ __forceinline__ void phase_sync()
 
 }  // namespace
 
-template <bool A_KMAJ, bool B_KMAJ>
-__global__ void __launch_bounds__(512)
-bf16_pingpong_kernel(Bf16Args p)
+// DIRECT: global->LDS DMA loads (false: register-staged 2-byte loads, for tile
+// offsets that are not 16-byte aligned).  EDGE: the tile overhangs the matrix in the
+// direction this wave loads, so lanes outside it are switched off.  Both are uniform
+// over the workgroup / wave and chosen once, so the loop body carries no branches for them.
+template <bool A_KMAJ, bool B_KMAJ, bool DIRECT, bool EDGE>
+__device__ __forceinline__ void pp_body(const Bf16Args &p)
 {
     // Load duty: waves 0-3 fetch the B halves, waves 4-7 the A halves (8 wave-loads
     // per half-block each), so the tile classes are instantiated for 4 loader waves.
@@ -92,30 +95,6 @@ bf16_pingpong_kernel(Bf16Args p)
     const uint32_t lane_off0 = group ? ATile::lane_off_bytes(0, lane, op_ld) : BTile::lane_off_bytes(0, lane, op_ld);
     const uint32_t lane_off1 = group ? ATile::lane_off_bytes(1, lane, op_ld) : BTile::lane_off_bytes(1, lane, op_ld);
     const int64_t g_stride = group ? ATile::instr_stride_bytes(op_ld) : BTile::instr_stride_bytes(op_ld);
-    // Only a tile on the ragged edge of the matrix needs lanes switched off.
-    const bool edge = op_first + (group ? PP_BM : PP_BN) > op_limit;
-
-    // Tile offsets live in device memory; a misaligned one sends the whole workgroup
-    // to the register-staged loader (2-byte loads).
-    // (The vote goes through the dynamic LDS: all 160 KiB are claimed by the slots,
-    // so nothing here may use static LDS.)
-    bool direct = true;
-    if (p.A_off) {
-        int bad = 0;
-        for (int i = tid; i < (int)p.batch; i += 512)
-            bad |= (((p.A_off[i] | p.B_off[i]) & 7) != 0);
-        const bool wave_bad = __builtin_amdgcn_ballot_w64(bad != 0) != 0;
-        LDS_AS int *vote = (LDS_AS int *)smem;
-        if (lane == 0)
-            vote[w] = wave_bad ? 1 : 0;
-        __syncthreads();
-        int any_bad = 0;
-#pragma unroll
-        for (int i = 0; i < PP_NW; ++i)
-            any_bad |= vote[i];
-        direct = any_bad == 0;
-        __syncthreads();
-    }
 
     // Load cursor of this wave's operand: next block's (batch index, k-block), its
     // source pointer and its ring slot.  Half-block 2t is A(t), 2t+1 is B(t); slot = index % 5.
@@ -124,30 +103,28 @@ bf16_pingpong_kernel(Bf16Args p)
     const uint16_t *ld_ptr = uniform_ptr(op_base + (op_off ? op_off[ld_i] : 0) + op_origin + ld_kb * op_kstep);
     int ld_slot = group ? 0 : 1;
 
-    auto issue_half = [&]() {
-        const uint32_t base = (uint32_t)ld_slot * PP_SLOT;
-        const char *g = (const char *)ld_ptr;
+    // One of the 8 wave-loads of this wave's next half-block.
+    auto issue_one = [&](int j) {
+        const int gi = wl * 8 + j;
+        const char *gj = (const char *)ld_ptr + (int64_t)gi * g_stride;
+        const uint32_t off = (j & 1) ? lane_off1 : lane_off0;
+        const uint32_t dst = (uint32_t)ld_slot * PP_SLOT + (uint32_t)gi * 1024u;
+        const bool on = !EDGE || (group ? ATile::lane_valid(gi, lane, op_first, op_limit)
+                                        : BTile::lane_valid(gi, lane, op_first, op_limit));
+        if (on) {
+            if constexpr (DIRECT) {
+                load16_to_lds_saddr(gj, off, (uint32_t)(size_t)(smem + dst));
+            } else {
+                const uint16_t *h = (const uint16_t *)(gj + off);
+                s16x8 v;
 #pragma unroll
-        for (int j = 0; j < 8; ++j) {
-            const int gi = wl * 8 + j;
-            const char *gj = g + (int64_t)gi * g_stride;
-            const uint32_t off = (j & 1) ? lane_off1 : lane_off0;
-            const uint32_t dst = base + (uint32_t)gi * 1024u;
-            const bool on = !edge || (group ? ATile::lane_valid(gi, lane, op_first, op_limit)
-                                            : BTile::lane_valid(gi, lane, op_first, op_limit));
-            if (on) {
-                if (direct) {
-                    load16_to_lds_saddr(gj, off, (uint32_t)(size_t)(smem + dst));
-                } else {
-                    const uint16_t *h = (const uint16_t *)(gj + off);
-                    s16x8 v;
-#pragma unroll
-                    for (int e = 0; e < 8; ++e)
-                        v[e] = (short)h[e];
-                    *(LDS_AS s16x8 *)(smem + dst + lane * 16) = v;
-                }
+                for (int e = 0; e < 8; ++e)
+                    v[e] = (short)h[e];
+                *(LDS_AS s16x8 *)(smem + dst + lane * 16) = v;
             }
         }
+    };
+    auto advance_loads = [&]() {
         ld_slot = ld_slot + 2 >= PP_SLOTS ? ld_slot + 2 - PP_SLOTS : ld_slot + 2;
         if (++ld_kb == kblocks) {
             ld_kb = 0;
@@ -157,6 +134,12 @@ bf16_pingpong_kernel(Bf16Args p)
         } else {
             ld_ptr += op_kstep;
         }
+    };
+    auto issue_half = [&]() {
+#pragma unroll
+        for (int j = 0; j < 8; ++j)
+            issue_one(j);
+        advance_loads();
     };
 
     f32x16 acc[PP_TN][PP_TM];
@@ -168,22 +151,32 @@ bf16_pingpong_kernel(Bf16Args p)
             for (int r = 0; r < 16; ++r)
                 acc[a][b][r] = 0.0f;
 
-    // Memory phase: every fragment of one k-block (4 slices of 16) into registers.
+    // Memory phase: every fragment of one k-block (4 slices of 16; 24 fragments) into
+    // registers, and - when `request` - this wave's 8 loads of a later half-block, one
+    // after every third fragment read so that the LDS reads complete while the wave
+    // is held by the address unit.  The loads only write slots nobody reads in this
+    // phase, so their order relative to the reads does not matter for correctness.
     bf16x8 fa[4][PP_TM], fb[4][PP_TN];
     int rd_slot = 0;                            // slot of A(t); B(t) is the next one
-    auto read_block = [&]() {
+    auto memory_phase = [&](bool request) {
         LDS_AS char *at = smem + (uint32_t)rd_slot * PP_SLOT;
         LDS_AS char *bt = smem + (uint32_t)(rd_slot + 1 == PP_SLOTS ? 0 : rd_slot + 1) * PP_SLOT;
-#pragma unroll
-        for (int s = 0; s < 4; ++s) {
-#pragma unroll
-            for (int t = 0; t < PP_TM; ++t)
-                fa[s][t] = ATile::read_frag(at, wm * PP_WM, t, s, lane);
-#pragma unroll
-            for (int t = 0; t < PP_TN; ++t)
-                fb[s][t] = BTile::read_frag(bt, wn * PP_WN, t, s, lane);
-        }
+        static_for<0, 8>([&](auto jc) {
+            constexpr int j = decltype(jc)::value;
+            static_for<0, 3>([&](auto ic) {
+                constexpr int id = 3 * j + decltype(ic)::value;
+                constexpr int sl = id / (PP_TM + PP_TN), q = id % (PP_TM + PP_TN);
+                if constexpr (q < PP_TM)
+                    fa[sl][q] = ATile::read_frag(at, wm * PP_WM, q, sl, lane);
+                else
+                    fb[sl][q - PP_TM] = BTile::read_frag(bt, wn * PP_WN, q - PP_TM, sl, lane);
+            });
+            if (request)
+                issue_one(j);
+        });
         rd_slot = rd_slot + 2 >= PP_SLOTS ? rd_slot + 2 - PP_SLOTS : rd_slot + 2;
+        if (request)
+            advance_loads();
     };
     // Compute phase: 32 MFMAs.  Operands are passed swapped (B fragment first) so the
     // 32x32 result is C^T: lane l owns row m = l%32 and 4 consecutive columns per
@@ -212,14 +205,9 @@ bf16_pingpong_kernel(Bf16Args p)
         for (int t = 0; t < n_iter; ++t) {
             // ---- memory phase.  Waves 0-3 request B(t+1): its slot held A(t-1), last
             // read one phase ago.  Waves 4-7 request A(t+2): its slot held B(t-1).
-            // The fragment reads go first: LDS reads issued behind global->LDS loads of
-            // the same wave do not complete until those loads have landed.
             const bool request = group == 0 ? (t + 1 < n_iter) : (t + 2 < n_iter);
-            read_block();
+            memory_phase(request);
             wait_lgkmcnt0();
-            __builtin_amdgcn_sched_barrier(0);
-            if (request)
-                issue_half();
             if (group == 1) {
                 // A(t+1), requested one block ago, must have landed before the barrier
                 // that precedes its first read; the 8 loads just issued may still fly.
@@ -275,6 +263,49 @@ bf16_pingpong_kernel(Bf16Args p)
         }
         __builtin_amdgcn_wave_barrier();
     });
+}
+
+template <bool A_KMAJ, bool B_KMAJ>
+__global__ void __launch_bounds__(512)
+bf16_pingpong_kernel(Bf16Args p)
+{
+    extern __shared__ __attribute__((aligned(1024))) char smem_generic[];
+    LDS_AS char *smem = (LDS_AS char *)smem_generic;
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
+
+    // Tile offsets live in device memory; a misaligned one sends the whole workgroup
+    // to the register-staged loader (2-byte loads).  The vote goes through the dynamic
+    // LDS: all 160 KiB are claimed by the slots, so nothing here may use static LDS.
+    bool direct = true;
+    if (p.A_off) {
+        int bad = 0;
+        for (int i = tid; i < (int)p.batch; i += 512)
+            bad |= (((p.A_off[i] | p.B_off[i]) & 7) != 0);
+        const bool wave_bad = __builtin_amdgcn_ballot_w64(bad != 0) != 0;
+        LDS_AS int *vote = (LDS_AS int *)smem;
+        if (lane == 0)
+            vote[w] = wave_bad ? 1 : 0;
+        __syncthreads();
+        int any_bad = 0;
+#pragma unroll
+        for (int i = 0; i < PP_NW; ++i)
+            any_bad |= vote[i];
+        direct = any_bad == 0;
+        __syncthreads();
+    }
+    // Does this wave's operand tile overhang the matrix?  (waves 4-7 load A, 0-3 load B)
+    int tm, tn;
+    tile_coords(blockIdx.x, p.tiles_m, p.tiles_n, tm, tn);
+    const bool edge = (w >> 2) ? ((int64_t)(tm + 1) * PP_BM > p.M) : ((int64_t)(tn + 1) * PP_BN > p.N);
+    if (direct) {
+        if (!edge) pp_body<A_KMAJ, B_KMAJ, true, false>(p);
+        else pp_body<A_KMAJ, B_KMAJ, true, true>(p);
+    } else {
+        if (!edge) pp_body<A_KMAJ, B_KMAJ, false, false>(p);
+        else pp_body<A_KMAJ, B_KMAJ, false, true>(p);
+    }
 }
 
 static hipError_t launch_pp(const Problem &p)

@@ -51,14 +51,17 @@ __device__ __forceinline__ const uint16_t *uniform_ptr(const uint16_t *p)
 // a 32-bit per-lane byte offset.  With 64-bit per-lane addresses the load's
 // address read competes with the MFMAs of the other wave on the SIMD for register
 // file bandwidth and issue takes ~2.5x longer (measured); this form does not.
-// lds_addr is the wave-uniform LDS byte address (goes to M0).  Not tracked by the
-// compiler's wait-count insertion: callers wait on vmcnt themselves.
+// lds_addr is the wave-uniform LDS byte address (goes to M0).  The statement carries
+// no "memory" clobber on purpose: with one, the compiler drains vmcnt and lgkmcnt
+// before every load.  It is therefore invisible to the compiler's wait-count
+// insertion and may be moved across ordinary LDS reads; callers wait on vmcnt
+// themselves and fence with volatile asm / barriers where order matters.
 __device__ __forceinline__ void load16_to_lds_saddr(const char *base, uint32_t lane_off, uint32_t lds_addr)
 {
     asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
                  :
                  : "s"(lds_addr), "v"(lane_off), "s"(base)
-                 : "memory", "m0");
+                 : "m0");
 }
 
 __device__ __forceinline__ void load16_to_lds(const uint16_t *g, uint32_t lds_byte, LDS_AS char *lds0)
