@@ -35,8 +35,12 @@ int choose_plan(const Problem &p, size_t workspace_bytes, int forced_variant, in
 {
     Plan plan{V_GENERIC, 1};
     if (bf16_mfma_eligible(p)) {
+        // 256x256 tiles once they can occupy most of the 256 CUs, else 128x128.
         const int64_t t256 = ((p.M + 255) / 256) * ((p.N + 255) / 256);
-        plan.variant = t256 >= 200 ? V_BF16_256x256 : V_BF16_128x128;
+        if (t256 >= 160)
+            plan.variant = bf16_pingpong_eligible(p) ? V_BF16_PP256 : V_BF16_256x256;
+        else
+            plan.variant = V_BF16_128x128;
     }
     if (forced_variant >= 0) {
         if (forced_variant >= V_COUNT || !variant_eligible(forced_variant, p))
