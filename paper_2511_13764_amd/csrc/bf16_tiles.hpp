@@ -58,9 +58,16 @@ __device__ __forceinline__ const uint16_t *uniform_ptr(const uint16_t *p)
 // themselves and fence with volatile asm / barriers where order matters.
 __device__ __forceinline__ void load16_to_lds_saddr(const char *base, uint32_t lane_off, uint32_t lds_addr)
 {
+    // readfirstlane: the "s" constraint alone does not move a value the compiler
+    // believes divergent into SGPRs (it is free when the value already is uniform).
+    const uint64_t b = (uint64_t)base;
+    const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)b);
+    const uint32_t hi = __builtin_amdgcn_readfirstlane((uint32_t)(b >> 32));
+    const uint64_t ub = ((uint64_t)hi << 32) | lo;
+    const uint32_t la = __builtin_amdgcn_readfirstlane(lds_addr);
     asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
                  :
-                 : "s"(lds_addr), "v"(lane_off), "s"(base)
+                 : "s"(la), "v"(lane_off), "s"(ub)
                  : "m0");
 }
 

@@ -11,6 +11,7 @@ const char *variant_name(int v)
     case V_BF16_256x256: return "bf16_256x256x64";
     case V_BF16_128x128: return "bf16_128x128x64";
     case V_BF16_PP256: return "bf16_pingpong_256x256x64";
+    case V_F32_128x128: return "f32_128x128x32";
     default: return "";
     }
 }
@@ -22,6 +23,7 @@ bool variant_eligible(int v, const Problem &p)
     case V_BF16_256x256:
     case V_BF16_128x128: return bf16_mfma_eligible(p);
     case V_BF16_PP256: return bf16_pingpong_eligible(p);
+    case V_F32_128x128: return f32_mfma_eligible(p);
     default: return false;
     }
 }
@@ -42,6 +44,8 @@ int choose_plan(const Problem &p, size_t workspace_bytes, int forced_variant, in
         else
             plan.variant = V_BF16_128x128;
     }
+    if (f32_mfma_eligible(p))
+        plan.variant = V_F32_128x128;
     if (forced_variant >= 0) {
         if (forced_variant >= V_COUNT || !variant_eligible(forced_variant, p))
             return BRGEMM_INVALID_ARG;
@@ -63,6 +67,7 @@ hipError_t launch_variant(int v, const Problem &p)
     case V_BF16_256x256: return launch_bf16_256x256(p);
     case V_BF16_128x128: return launch_bf16_128x128(p);
     case V_BF16_PP256: return launch_bf16_pingpong(p);
+    case V_F32_128x128: return launch_f32_128x128(p);
     default: return hipErrorInvalidValue;
     }
 }

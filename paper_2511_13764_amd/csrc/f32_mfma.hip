@@ -1,0 +1,296 @@
+// Tuned fp32 GEMM kernel for gfx950: 128 x 128 x 32 workgroup tile, 4 wavefronts,
+// each keeping a 64 x 64 accumulator tile (four v_mfma_f32_32x32x2_f32 tiles, 64
+// registers) in registers for the whole K loop - the fp32 branch of Algorithm 1
+// (broadcast a column of A, load a chunk of B, fused multiply-add into the resident
+// accumulators), with the matrix instruction in the role of vector.fma.
+//
+// fp32 MFMA runs at 1/16 of the bf16 rate, so per k-block the 64 MFMAs of a wave
+// take ~4096 cycles against 32 KiB of loads and 64 KiB of LDS reads per CU: the
+// kernel is bound by the matrix pipe and a two-stage LDS pipeline with one wave per
+// SIMD is enough.  Global -> LDS copies use the scalar-base form of
+// global_load_lds_dwordx4 and are spread between the MFMA groups.
+//
+// LDS images.  An operand whose contiguous direction is k keeps 128-byte rows with
+// the 16-byte chunk c of row r at position c ^ ((r >> 1) & 7) (same image as the
+// bf16 kernels); a lane fetches 4 consecutive k with one 128-bit read and feeds them
+// to 4 successive MFMAs.  The k order inside the MFMA is free as long as both
+// operands agree: MFMA (j, t) contracts k = 8j + t (lanes 0-31) and 8j + 4 + t
+// (lanes 32-63).  An operand whose contiguous direction is m or n keeps 512-byte
+// k-rows; the lane needs one element per MFMA (32-bit read), and the chunk position
+// is c ^ 8 for k-rows with bit 2 set so that the two half-waves hit different banks.
+#include "bf16_tiles.hpp"
+
+namespace brg {
+
+namespace {
+
+constexpr int FB = 128;                 // tile edge (M and N)
+constexpr int FK = 32;                  // k-block (floats) = 128 bytes
+constexpr uint32_t F_OP_BYTES = FB * FK * 4;        // 16 KiB per operand per stage
+constexpr uint32_t F_STAGE = 2 * F_OP_BYTES;
+
+struct F32Args {
+    int64_t M, N, K;
+    const float *A;
+    int64_t lda;
+    const float *B;
+    int64_t ldb;
+    Epilogue epi;
+    int split;
+    float *partial;
+    int tiles_m, tiles_n;
+};
+
+// k-contiguous operand: reuse the 128-byte-row image of the bf16 tiles (a float row
+// of 32 k is byte-identical to a bf16 row of 64 k); leading dimensions are passed in
+// 2-byte units.
+typedef KMajorTile<FB, 4> FKTile;
+
+// m/n-contiguous operand: 32 k-rows of 128 floats.
+struct FMNTile {
+    static constexpr int kPerWave = 4;      // 16 wave-loads of 2 k-rows each
+    __device__ static int64_t instr_stride_bytes(int64_t ld) { return 2 * ld * 4; }
+    // variant = (g >> 1) & 1 of wave-load g (k-row bit 2)
+    __device__ static uint32_t lane_off_bytes(int variant, int lane, int64_t ld)
+    {
+        const int c = (lane & 31) ^ (variant << 3);
+        return (uint32_t)((int64_t)(lane >> 5) * ld * 4 + 16 * c);
+    }
+    __device__ static bool lane_valid(int g, int lane, int64_t col0, int64_t col_limit)
+    {
+        const int c = (lane & 31) ^ (((g >> 1) & 1) << 3);
+        return col0 + 4 * c < col_limit;
+    }
+    // element k = 8j + 4*(lane/32) + t of column col_base + t32*32 + lane%32
+    __device__ static float read(LDS_AS char *tile, int col_base, int t32, int j, int t, int lane)
+    {
+        const int h = lane >> 5;
+        const int k = 8 * j + 4 * h + t;
+        const int col = col_base + t32 * 32 + (lane & 31);
+        const int c = (col >> 2) ^ (h << 3);
+        return *(LDS_AS float *)(tile + k * 512 + (c << 4) + (col & 3) * 4);
+    }
+};
+
+}  // namespace
+
+template <bool A_KMAJ, bool B_KMAJ>
+__global__ void __launch_bounds__(256)
+f32_mfma_kernel(F32Args p)
+{
+    extern __shared__ __attribute__((aligned(1024))) char smem_generic[];
+    LDS_AS char *smem = (LDS_AS char *)smem_generic;
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wm = w >> 1, wn = w & 1;
+
+    int tm, tn;
+    tile_coords(blockIdx.x, p.tiles_m, p.tiles_n, tm, tn);
+    const int64_t m0 = (int64_t)tm * FB, n0 = (int64_t)tn * FB;
+
+    const int kblocks = (int)(p.K / FK);
+    const int per = (kblocks + p.split - 1) / p.split;
+    const int it_begin = (int)blockIdx.y * per;
+    const int it_end = (it_begin + per < kblocks) ? it_begin + per : kblocks;
+    const int n_iter = it_end - it_begin;
+
+    // Global -> LDS addressing: scalar base + wave-load index * stride + lane offset.
+    const int64_t a_stride = A_KMAJ ? FKTile::instr_stride_bytes(2 * p.lda) : FMNTile::instr_stride_bytes(p.lda);
+    const int64_t b_stride = B_KMAJ ? FKTile::instr_stride_bytes(2 * p.ldb) : FMNTile::instr_stride_bytes(p.ldb);
+    const uint32_t a_off0 = A_KMAJ ? FKTile::lane_off_bytes(0, lane, 2 * p.lda) : FMNTile::lane_off_bytes(0, lane, p.lda);
+    const uint32_t a_off1 = A_KMAJ ? FKTile::lane_off_bytes(1, lane, 2 * p.lda) : FMNTile::lane_off_bytes(1, lane, p.lda);
+    const uint32_t b_off0 = B_KMAJ ? FKTile::lane_off_bytes(0, lane, 2 * p.ldb) : FMNTile::lane_off_bytes(0, lane, p.ldb);
+    const uint32_t b_off1 = B_KMAJ ? FKTile::lane_off_bytes(1, lane, 2 * p.ldb) : FMNTile::lane_off_bytes(1, lane, p.ldb);
+    const int64_t a_kstep = A_KMAJ ? (int64_t)FK : (int64_t)FK * p.lda;      // floats per k-block
+    const int64_t b_kstep = B_KMAJ ? (int64_t)FK : (int64_t)FK * p.ldb;
+    const float *ld_a = p.A + (A_KMAJ ? m0 * p.lda : m0) + (int64_t)it_begin * a_kstep;
+    const float *ld_b = p.B + (B_KMAJ ? n0 * p.ldb : n0) + (int64_t)it_begin * b_kstep;
+
+    // Wave-load q (0..7) of this wave for the block at ld_a / ld_b: 4 of A, then 4 of B.
+    auto issue_one = [&](int stage, int q) {
+        const bool is_a = q < 4;
+        const int g = w * 4 + (q & 3);
+        const char *base = is_a ? (const char *)ld_a + (int64_t)g * a_stride : (const char *)ld_b + (int64_t)g * b_stride;
+        bool variant, on;
+        if (is_a) {
+            variant = A_KMAJ ? (g & 1) : ((g >> 1) & 1);
+            on = A_KMAJ ? FKTile::lane_valid(g, lane, m0, p.M) : FMNTile::lane_valid(g, lane, m0, p.M);
+        } else {
+            variant = B_KMAJ ? (g & 1) : ((g >> 1) & 1);
+            on = B_KMAJ ? FKTile::lane_valid(g, lane, n0, p.N) : FMNTile::lane_valid(g, lane, n0, p.N);
+        }
+        const uint32_t off = is_a ? (variant ? a_off1 : a_off0) : (variant ? b_off1 : b_off0);
+        const uint32_t dst = (uint32_t)stage * F_STAGE + (is_a ? 0u : F_OP_BYTES) + (uint32_t)g * 1024u;
+        if (on)
+            load16_to_lds_saddr(base, off, (uint32_t)(size_t)(smem + dst));
+    };
+    auto advance = [&]() { ld_a += a_kstep; ld_b += b_kstep; };
+
+    f32x16 acc[2][2];
+#pragma unroll
+    for (int a = 0; a < 2; ++a)
+#pragma unroll
+        for (int b = 0; b < 2; ++b)
+#pragma unroll
+            for (int r = 0; r < 16; ++r)
+                acc[a][b][r] = 0.0f;
+
+    // Fragments of one j-step (8 k): per 32-row MFMA tile 4 floats per lane.
+    f32x4 fa[2][2], fb[2][2];          // [buffer][tile]
+    auto read_step = [&](int stage, int j, int buf) {
+        LDS_AS char *at = smem + (uint32_t)stage * F_STAGE;
+        LDS_AS char *bt = at + F_OP_BYTES;
+#pragma unroll
+        for (int t = 0; t < 2; ++t) {
+            if (A_KMAJ) {
+                fa[buf][t] = *(LDS_AS f32x4 *)(at + FKTile::frag_byte(wm * 64, t, j, lane));
+            } else {
+#pragma unroll
+                for (int e = 0; e < 4; ++e)
+                    fa[buf][t][e] = FMNTile::read(at, wm * 64, t, j, e, lane);
+            }
+            if (B_KMAJ) {
+                fb[buf][t] = *(LDS_AS f32x4 *)(bt + FKTile::frag_byte(wn * 64, t, j, lane));
+            } else {
+#pragma unroll
+                for (int e = 0; e < 4; ++e)
+                    fb[buf][t][e] = FMNTile::read(bt, wn * 64, t, j, e, lane);
+            }
+        }
+    };
+    // 16 MFMAs.  Operands swapped (B first): the 32x32 result is C^T, so a lane owns
+    // row m = lane%32 and 4 consecutive columns per group of 4 registers.
+    auto mma_step = [&](int buf) {
+#pragma unroll
+        for (int e = 0; e < 4; ++e)
+#pragma unroll
+            for (int a = 0; a < 2; ++a)
+#pragma unroll
+                for (int b = 0; b < 2; ++b)
+                    acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x2f32(fb[buf][a][e], fa[buf][b][e], acc[a][b], 0, 0, 0);
+    };
+
+    if (n_iter > 0) {
+#pragma unroll
+        for (int q = 0; q < 8; ++q)
+            issue_one(0, q);
+        advance();
+        wait_vmcnt0();
+        __syncthreads();
+
+        for (int it = 0; it < n_iter; ++it) {
+            const int cur = it & 1;
+            const bool more = it + 1 < n_iter;
+            read_step(cur, 0, 0);
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                if (j < 3)
+                    read_step(cur, j + 1, (j + 1) & 1);
+                mma_step(j & 1);
+                // two of the next block's eight wave-loads after each group of MFMAs
+                __builtin_amdgcn_sched_barrier(0);
+                if (more) {
+                    issue_one(cur ^ 1, 2 * j);
+                    issue_one(cur ^ 1, 2 * j + 1);
+                }
+                __builtin_amdgcn_sched_barrier(0);
+            }
+            if (more)
+                advance();
+            wait_vmcnt0();
+            __syncthreads();
+        }
+    }
+
+    // ---- epilogue: beta*C, bias, ReLU, store (or raw partial tile for a split)
+    const int64_t m_base = m0 + wm * 64 + (lane & 31);
+    const int64_t n_base = n0 + wn * 64 + 4 * (lane >> 5);
+    if (p.split > 1) {
+        float *part = p.partial + (int64_t)blockIdx.y * p.M * p.N;
+        const bool vec = (p.N & 3) == 0;
+        static_for<0, 2>([&](auto bc) {
+            constexpr int b = decltype(bc)::value;
+            const int64_t m = m_base + b * 32;
+            if (m < p.M) {
+                static_for<0, 8>([&](auto aq) {
+                    constexpr int a = decltype(aq)::value / 4, q = decltype(aq)::value % 4;
+                    const int64_t n = n_base + a * 32 + q * 8;
+                    store4_partial(part + m * p.N + n, p.N - n, vec, acc[a][b][4 * q + 0], acc[a][b][4 * q + 1],
+                                   acc[a][b][4 * q + 2], acc[a][b][4 * q + 3]);
+                });
+            }
+        });
+    } else {
+        const bool vec = (p.epi.ldc & 3) == 0 && (((uintptr_t)p.epi.C) & 15) == 0;
+        static_for<0, 2>([&](auto bc) {
+            constexpr int b = decltype(bc)::value;
+            const int64_t m = m_base + b * 32;
+            if (m < p.M) {
+                static_for<0, 8>([&](auto aq) {
+                    constexpr int a = decltype(aq)::value / 4, q = decltype(aq)::value % 4;
+                    const int64_t n = n_base + a * 32 + q * 8;
+                    store4_epilogue(p.epi, m, n, p.N - n, vec, acc[a][b][4 * q + 0], acc[a][b][4 * q + 1],
+                                    acc[a][b][4 * q + 2], acc[a][b][4 * q + 3]);
+                });
+            }
+        });
+    }
+}
+
+hipError_t launch_f32_128x128(const Problem &p)
+{
+    F32Args a;
+    a.M = p.M; a.N = p.N; a.K = p.K;
+    a.A = (const float *)p.A; a.lda = p.lda;
+    a.B = (const float *)p.B; a.ldb = p.ldb;
+    a.epi.beta = p.beta; a.epi.C = p.C; a.epi.ldc = p.ldc; a.epi.c_f32 = 1;
+    a.epi.bias = p.bias; a.epi.relu = p.relu;
+    a.split = p.split; a.partial = p.partial;
+    a.tiles_m = (int)((p.M + FB - 1) / FB);
+    a.tiles_n = (int)((p.N + FB - 1) / FB);
+    const dim3 grid((unsigned)(a.tiles_m * a.tiles_n), (unsigned)p.split);
+    const size_t lds = 2 * (size_t)F_STAGE;
+    const bool ak = p.transA == 0, bk = p.transB == 1;
+    void (*kern)(F32Args) = nullptr;
+    if (ak && bk) kern = f32_mfma_kernel<true, true>;
+    else if (ak && !bk) kern = f32_mfma_kernel<true, false>;
+    else if (!ak && bk) kern = f32_mfma_kernel<false, true>;
+    else kern = f32_mfma_kernel<false, false>;
+    static thread_local const void *configured[4] = {nullptr};
+    bool done = false;
+    for (const void *c : configured)
+        done = done || c == (const void *)kern;
+    if (!done) {
+        hipError_t e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e != hipSuccess)
+            return e;
+        for (auto &c : configured)
+            if (!c) { c = (const void *)kern; break; }
+    }
+    hipLaunchKernelGGL(kern, grid, dim3(256), lds, p.stream, a);
+    return hipGetLastError();
+}
+
+// fp32 operands, plain GEMM (no tile offsets), K a multiple of 32, 16-byte aligned
+// bases, leading dimensions multiples of 4, and an m/n-contiguous operand must have
+// its extent a multiple of 4 (whole 16-byte chunks).
+bool f32_mfma_eligible(const Problem &p)
+{
+    if (p.in_bf16 || !p.c_f32 || p.A_off || p.batch != 1)
+        return false;
+    if (p.K % FK != 0)
+        return false;
+    if (((uintptr_t)p.A & 15) || ((uintptr_t)p.B & 15) || (p.lda & 3) || (p.ldb & 3))
+        return false;
+    if (p.transA == 1 && (p.M & 3))
+        return false;
+    if (p.transB == 0 && (p.N & 3))
+        return false;
+    if (p.lda >= (1 << 21) || p.ldb >= (1 << 21) || p.M * p.N >= ((int64_t)1 << 40))
+        return false;
+    return true;
+}
+
+}  // namespace brg
