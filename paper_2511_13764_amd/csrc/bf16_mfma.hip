@@ -54,14 +54,17 @@ bf16_mfma_kernel(Bf16Args p)
     const int it_end = (it_begin + per < total) ? it_begin + per : total;
     const int n_iter = it_end - it_begin;
 
-    // Per-lane global source offsets (elements), fixed for the whole kernel.
-    int64_t a_src[ATile::kPerWave], b_src[BTile::kPerWave];
+    // Per-lane source offsets (bytes from the block origin), fixed for the whole kernel;
+    // the block origin is a wave-uniform pointer (scalar-base form of the loads).
+    uint32_t a_src[ATile::kPerWave], b_src[BTile::kPerWave];
 #pragma unroll
     for (int j = 0; j < ATile::kPerWave; ++j)
-        a_src[j] = ATile::src_offset(w, j, lane, m0, p.M, p.lda);
+        a_src[j] = ATile::src_rel_bytes(w, j, lane, m0, p.M, p.lda);
 #pragma unroll
     for (int j = 0; j < BTile::kPerWave; ++j)
-        b_src[j] = BTile::src_offset(w, j, lane, n0, p.N, p.ldb);
+        b_src[j] = BTile::src_rel_bytes(w, j, lane, n0, p.N, p.ldb);
+    const int64_t a_origin = A_KMAJ ? m0 * p.lda : m0;
+    const int64_t b_origin = B_KMAJ ? n0 * p.ldb : n0;
     const int64_t a_kstep = A_KMAJ ? (int64_t)BK : (int64_t)BK * p.lda;
     const int64_t b_kstep = B_KMAJ ? (int64_t)BK : (int64_t)BK * p.ldb;
 
@@ -69,8 +72,8 @@ bf16_mfma_kernel(Bf16Args p)
     // operand pointers that go with it.  Advanced without divisions.
     int ld_i = n_iter > 0 ? it_begin / kblocks : 0;
     int ld_kb = n_iter > 0 ? it_begin - ld_i * kblocks : 0;
-    const uint16_t *ld_a = p.A + (p.A_off ? p.A_off[ld_i] : 0) + ld_kb * a_kstep;
-    const uint16_t *ld_b = p.B + (p.B_off ? p.B_off[ld_i] : 0) + ld_kb * b_kstep;
+    const uint16_t *ld_a = uniform_ptr(p.A + (p.A_off ? p.A_off[ld_i] : 0) + a_origin + ld_kb * a_kstep);
+    const uint16_t *ld_b = uniform_ptr(p.B + (p.B_off ? p.B_off[ld_i] : 0) + b_origin + ld_kb * b_kstep);
     // Tile offsets live in device memory, so their alignment cannot be checked on the
     // host: if any A_off / B_off is not a multiple of 8 elements (16 bytes) the whole
     // workgroup stages its blocks through registers with 2-byte loads instead.
@@ -81,7 +84,8 @@ bf16_mfma_kernel(Bf16Args p)
             ok &= (((p.A_off[i] | p.B_off[i]) & 7) == 0);
         direct = __syncthreads_and(ok) != 0;
     }
-    auto staged16 = [&](const uint16_t *g, uint32_t lds_byte) {
+    auto staged16 = [&](const char *gc, uint32_t lds_byte) {
+        const uint16_t *g = (const uint16_t *)gc;
         s16x8 v;
 #pragma unroll
         for (int e = 0; e < 8; ++e)
@@ -90,27 +94,28 @@ bf16_mfma_kernel(Bf16Args p)
     };
     auto issue_loads = [&](int stage) {
         const uint32_t base = (uint32_t)stage * STAGE;
+        const char *ga = (const char *)ld_a, *gb = (const char *)ld_b;
         if (direct) {
 #pragma unroll
             for (int j = 0; j < ATile::kPerWave; ++j)
-                load16_to_lds(ld_a + a_src[j], base + ATile::dst_byte(w, j), smem);
+                load16_to_lds_saddr(ga, a_src[j], (uint32_t)(size_t)(smem + base + ATile::dst_byte(w, j)));
 #pragma unroll
             for (int j = 0; j < BTile::kPerWave; ++j)
-                load16_to_lds(ld_b + b_src[j], base + A_BYTES + BTile::dst_byte(w, j), smem);
+                load16_to_lds_saddr(gb, b_src[j], (uint32_t)(size_t)(smem + base + A_BYTES + BTile::dst_byte(w, j)));
         } else {
 #pragma unroll
             for (int j = 0; j < ATile::kPerWave; ++j)
-                staged16(ld_a + a_src[j], base + ATile::dst_byte(w, j));
+                staged16(ga + a_src[j], base + ATile::dst_byte(w, j));
 #pragma unroll
             for (int j = 0; j < BTile::kPerWave; ++j)
-                staged16(ld_b + b_src[j], base + A_BYTES + BTile::dst_byte(w, j));
+                staged16(gb + b_src[j], base + A_BYTES + BTile::dst_byte(w, j));
         }
         if (++ld_kb == kblocks) {
             ld_kb = 0;
             ++ld_i;
             if (p.A_off && ld_i < (int)p.batch) {
-                ld_a = p.A + p.A_off[ld_i];
-                ld_b = p.B + p.B_off[ld_i];
+                ld_a = uniform_ptr(p.A + p.A_off[ld_i] + a_origin);
+                ld_b = uniform_ptr(p.B + p.B_off[ld_i] + b_origin);
             }
         } else {
             ld_a += a_kstep;
@@ -282,6 +287,8 @@ bool bf16_mfma_eligible(const Problem &p)
     if (p.transA == 1 && (p.M & 7))
         return false;
     if (p.transB == 0 && (p.N & 7))
+        return false;
+    if (p.lda >= (1 << 22) || p.ldb >= (1 << 22))
         return false;
     if (p.batch * (p.K / BK) >= ((int64_t)1 << 31) || p.M * p.N >= ((int64_t)1 << 40))
         return false;

@@ -33,16 +33,53 @@ static size_t split_bytes(const Problem &p, int split)
     return split > 1 ? (size_t)split * (size_t)p.M * (size_t)p.N * sizeof(float) : 0;
 }
 
+// Reduction split for a grid of 128x128 tiles that cannot fill the chip (skinny M,
+// small squares, batch-reduce into a small C).  A rough time model, in microseconds,
+// with constants measured on MI355X: a 128x128x64 k-block costs ~0.45 us per
+// workgroup, 512 workgroups run at once (two per CU), streaming the operands cannot
+// beat ~5 TB/s, and the fixed-order reduction moves split*M*N*8 bytes at ~3 TB/s plus
+// a second launch.
+static int split_for_small_grid(const Problem &p, size_t workspace_bytes)
+{
+    const double tiles = (double)((p.M + 127) / 128) * (double)((p.N + 127) / 128);
+    const double kblocks = (double)p.batch * (double)(p.K / 64);
+    const double operand_bytes = 2.0 * ((double)p.M + (double)p.N) * (double)p.K * (double)p.batch;
+    static const int candidates[] = {1, 2, 3, 4, 5, 6, 8, 10, 12, 16};
+    int best = 1;
+    double best_t = 1e30;
+    for (int s : candidates) {
+        if (s > kMaxSplit || (s > 1 && kblocks / s < 2.0))
+            continue;
+        if (s > 1 && (size_t)s * (size_t)p.M * (size_t)p.N * sizeof(float) > workspace_bytes)
+            continue;
+        const double rounds = (double)(int64_t)((tiles * s + 511.0) / 512.0);
+        double t_main = rounds * (kblocks / s) * 0.45;
+        const double t_stream = operand_bytes / 5.0e6;
+        if (t_main < t_stream)
+            t_main = t_stream;
+        const double t_reduce = s > 1 ? 4.0 + (double)s * (double)p.M * (double)p.N * 8.0 / 3.0e6 : 0.0;
+        const double t = 6.0 + t_main + t_reduce;
+        if (t < best_t * 0.97) {     // prefer the smaller split on near ties
+            best_t = t;
+            best = s;
+        }
+    }
+    return best;
+}
+
 int choose_plan(const Problem &p, size_t workspace_bytes, int forced_variant, int forced_split, Plan *out)
 {
     Plan plan{V_GENERIC, 1};
     if (bf16_mfma_eligible(p)) {
-        // 256x256 tiles once they can occupy most of the 256 CUs, else 128x128.
+        // 256x256 tiles once they can occupy most of the 256 CUs, else 128x128, whose
+        // workgroups fit two to a CU.
         const int64_t t256 = ((p.M + 255) / 256) * ((p.N + 255) / 256);
-        if (t256 >= 160)
+        if (t256 >= 160) {
             plan.variant = bf16_pingpong_eligible(p) ? V_BF16_PP256 : V_BF16_256x256;
-        else
+        } else {
             plan.variant = V_BF16_128x128;
+            plan.split = split_for_small_grid(p, workspace_bytes);
+        }
     }
     if (f32_mfma_eligible(p))
         plan.variant = V_F32_128x128;
