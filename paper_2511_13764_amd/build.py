@@ -13,7 +13,7 @@ LIB = os.path.join(HERE, "libbrgemm_gfx950.so")
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fno-gpu-rdc",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
-         "-Wall", "-Wno-unused-command-line-argument"]
+         "-Wall", "-Wno-unused-command-line-argument", "-Wno-inline-asm"]
 
 
 def _compile(src):

@@ -35,9 +35,9 @@ static size_t split_bytes(const Problem &p, int split)
 
 // Reduction split for a grid of 128x128 tiles that cannot fill the chip (skinny M,
 // small squares, batch-reduce into a small C).  A rough time model, in microseconds,
-// with constants measured on MI355X: a 128x128x64 k-block costs ~0.45 us per
-// workgroup, 512 workgroups run at once (two per CU), streaming the operands cannot
-// beat ~5 TB/s, and the fixed-order reduction moves split*M*N*8 bytes at ~3 TB/s plus
+// with constants fitted to split sweeps on MI355X: a 128x128x64 k-block costs ~0.57 us
+// per workgroup, 512 workgroups run at once (two per CU), streaming the operands cannot
+// beat ~8 TB/s (they sit in the Infinity Cache when a call repeats), and the fixed-order reduction moves split*M*N*8 bytes at ~3 TB/s plus
 // a second launch.
 static int split_for_small_grid(const Problem &p, size_t workspace_bytes)
 {
@@ -53,8 +53,8 @@ static int split_for_small_grid(const Problem &p, size_t workspace_bytes)
         if (s > 1 && (size_t)s * (size_t)p.M * (size_t)p.N * sizeof(float) > workspace_bytes)
             continue;
         const double rounds = (double)(int64_t)((tiles * s + 511.0) / 512.0);
-        double t_main = rounds * (kblocks / s) * 0.45;
-        const double t_stream = operand_bytes / 5.0e6;
+        double t_main = rounds * (kblocks / s) * 0.57;
+        const double t_stream = operand_bytes / 8.0e6;
         if (t_main < t_stream)
             t_main = t_stream;
         const double t_reduce = s > 1 ? 4.0 + (double)s * (double)p.M * (double)p.N * 8.0 / 3.0e6 : 0.0;

@@ -1,14 +1,14 @@
-// Tuned fp32 GEMM kernel for gfx950: 128 x 128 x 32 workgroup tile, 4 wavefronts,
-// each keeping a 64 x 64 accumulator tile (four v_mfma_f32_32x32x2_f32 tiles, 64
+// Tuned fp32 GEMM kernel for gfx950: 128 x 128 x 32 workgroup tile, 8 wavefronts,
+// each keeping a 64 x 32 accumulator tile (two v_mfma_f32_32x32x2_f32 tiles, 32
 // registers) in registers for the whole K loop - the fp32 branch of Algorithm 1
 // (broadcast a column of A, load a chunk of B, fused multiply-add into the resident
 // accumulators), with the matrix instruction in the role of vector.fma.
 //
-// fp32 MFMA runs at 1/16 of the bf16 rate, so per k-block the 64 MFMAs of a wave
-// take ~4096 cycles against 32 KiB of loads and 64 KiB of LDS reads per CU: the
-// kernel is bound by the matrix pipe and a two-stage LDS pipeline with one wave per
-// SIMD is enough.  Global -> LDS copies use the scalar-base form of
-// global_load_lds_dwordx4 and are spread between the MFMA groups.
+// fp32 MFMA runs at 1/16 of the bf16 rate, so per k-block the 64 MFMAs of a SIMD
+// take ~4096 cycles against 32 KiB of loads and ~100 KiB of LDS reads per CU: the
+// kernel is bound by the matrix pipe and a two-stage LDS pipeline is enough; two
+// waves per SIMD cover each other's load issue and LDS latency.  Global -> LDS copies
+// use the scalar-base form of global_load_lds_dwordx4, spread between the MFMA groups.
 //
 // LDS images.  An operand whose contiguous direction is k keeps 128-byte rows with
 // the 16-byte chunk c of row r at position c ^ ((r >> 1) & 7) (same image as the
@@ -48,7 +48,6 @@ typedef KMajorTile<FB, 4> FKTile;
 
 // m/n-contiguous operand: 32 k-rows of 128 floats.
 struct FMNTile {
-    static constexpr int kPerWave = 4;      // 16 wave-loads of 2 k-rows each
     __device__ static int64_t instr_stride_bytes(int64_t ld) { return 2 * ld * 4; }
     // variant = (g >> 1) & 1 of wave-load g (k-row bit 2)
     __device__ static uint32_t lane_off_bytes(int variant, int lane, int64_t ld)
@@ -74,17 +73,24 @@ struct FMNTile {
 
 }  // namespace
 
-template <bool A_KMAJ, bool B_KMAJ>
-__global__ void __launch_bounds__(256)
+// NW = 8: two waves per SIMD (wave tile 64 x 32), which hides each wave's load issue
+// and LDS latency behind the other's MFMAs; NW = 4: one wave per SIMD (wave tile 64 x 64).
+template <bool A_KMAJ, bool B_KMAJ, int NW>
+__global__ void __launch_bounds__(NW * 64)
 f32_mfma_kernel(F32Args p)
 {
+    constexpr int WNW = NW / 2;             // waves along N
+    constexpr int WN = FB / WNW;            // wave tile width: 64 or 32
+    constexpr int TN = WN / 32;             // 32-column MFMA tiles per wave
+    constexpr int PER_OP = 16 / NW;         // wave-loads per wave per operand per block
+
     extern __shared__ __attribute__((aligned(1024))) char smem_generic[];
     LDS_AS char *smem = (LDS_AS char *)smem_generic;
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int wm = w >> 1, wn = w & 1;
+    const int wm = w / WNW, wn = w % WNW;
 
     int tm, tn;
     tile_coords(blockIdx.x, p.tiles_m, p.tiles_n, tm, tn);
@@ -108,10 +114,10 @@ f32_mfma_kernel(F32Args p)
     const float *ld_a = p.A + (A_KMAJ ? m0 * p.lda : m0) + (int64_t)it_begin * a_kstep;
     const float *ld_b = p.B + (B_KMAJ ? n0 * p.ldb : n0) + (int64_t)it_begin * b_kstep;
 
-    // Wave-load q (0..7) of this wave for the block at ld_a / ld_b: 4 of A, then 4 of B.
+    // Wave-load q (0..2*PER_OP-1) of this wave for the block at ld_a / ld_b: A first, then B.
     auto issue_one = [&](int stage, int q) {
-        const bool is_a = q < 4;
-        const int g = w * 4 + (q & 3);
+        const bool is_a = q < PER_OP;
+        const int g = w * PER_OP + (q % PER_OP);
         const char *base = is_a ? (const char *)ld_a + (int64_t)g * a_stride : (const char *)ld_b + (int64_t)g * b_stride;
         bool variant, on;
         if (is_a) {
@@ -128,9 +134,9 @@ f32_mfma_kernel(F32Args p)
     };
     auto advance = [&]() { ld_a += a_kstep; ld_b += b_kstep; };
 
-    f32x16 acc[2][2];
+    f32x16 acc[TN][2];
 #pragma unroll
-    for (int a = 0; a < 2; ++a)
+    for (int a = 0; a < TN; ++a)
 #pragma unroll
         for (int b = 0; b < 2; ++b)
 #pragma unroll
@@ -138,7 +144,7 @@ f32_mfma_kernel(F32Args p)
                 acc[a][b][r] = 0.0f;
 
     // Fragments of one j-step (8 k): per 32-row MFMA tile 4 floats per lane.
-    f32x4 fa[2][2], fb[2][2];          // [buffer][tile]
+    f32x4 fa[2][2], fb[2][TN];         // [buffer][tile]
     auto read_step = [&](int stage, int j, int buf) {
         LDS_AS char *at = smem + (uint32_t)stage * F_STAGE;
         LDS_AS char *bt = at + F_OP_BYTES;
@@ -151,22 +157,25 @@ f32_mfma_kernel(F32Args p)
                 for (int e = 0; e < 4; ++e)
                     fa[buf][t][e] = FMNTile::read(at, wm * 64, t, j, e, lane);
             }
+        }
+#pragma unroll
+        for (int t = 0; t < TN; ++t) {
             if (B_KMAJ) {
-                fb[buf][t] = *(LDS_AS f32x4 *)(bt + FKTile::frag_byte(wn * 64, t, j, lane));
+                fb[buf][t] = *(LDS_AS f32x4 *)(bt + FKTile::frag_byte(wn * WN, t, j, lane));
             } else {
 #pragma unroll
                 for (int e = 0; e < 4; ++e)
-                    fb[buf][t][e] = FMNTile::read(bt, wn * 64, t, j, e, lane);
+                    fb[buf][t][e] = FMNTile::read(bt, wn * WN, t, j, e, lane);
             }
         }
     };
-    // 16 MFMAs.  Operands swapped (B first): the 32x32 result is C^T, so a lane owns
+    // 8 * TN MFMAs.  Operands swapped (B first): the 32x32 result is C^T, so a lane owns
     // row m = lane%32 and 4 consecutive columns per group of 4 registers.
     auto mma_step = [&](int buf) {
 #pragma unroll
         for (int e = 0; e < 4; ++e)
 #pragma unroll
-            for (int a = 0; a < 2; ++a)
+            for (int a = 0; a < TN; ++a)
 #pragma unroll
                 for (int b = 0; b < 2; ++b)
                     acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x2f32(fb[buf][a][e], fa[buf][b][e], acc[a][b], 0, 0, 0);
@@ -174,7 +183,7 @@ f32_mfma_kernel(F32Args p)
 
     if (n_iter > 0) {
 #pragma unroll
-        for (int q = 0; q < 8; ++q)
+        for (int q = 0; q < 2 * PER_OP; ++q)
             issue_one(0, q);
         advance();
         wait_vmcnt0();
@@ -189,11 +198,12 @@ f32_mfma_kernel(F32Args p)
                 if (j < 3)
                     read_step(cur, j + 1, (j + 1) & 1);
                 mma_step(j & 1);
-                // two of the next block's eight wave-loads after each group of MFMAs
+                // a quarter of this wave's loads for the next block after each group of MFMAs
                 __builtin_amdgcn_sched_barrier(0);
                 if (more) {
-                    issue_one(cur ^ 1, 2 * j);
-                    issue_one(cur ^ 1, 2 * j + 1);
+#pragma unroll
+                    for (int q = 0; q < PER_OP / 2; ++q)
+                        issue_one(cur ^ 1, j * (PER_OP / 2) + q);
                 }
                 __builtin_amdgcn_sched_barrier(0);
             }
@@ -206,7 +216,7 @@ f32_mfma_kernel(F32Args p)
 
     // ---- epilogue: beta*C, bias, ReLU, store (or raw partial tile for a split)
     const int64_t m_base = m0 + wm * 64 + (lane & 31);
-    const int64_t n_base = n0 + wn * 64 + 4 * (lane >> 5);
+    const int64_t n_base = n0 + wn * WN + 4 * (lane >> 5);
     if (p.split > 1) {
         float *part = p.partial + (int64_t)blockIdx.y * p.M * p.N;
         const bool vec = (p.N & 3) == 0;
@@ -214,7 +224,7 @@ f32_mfma_kernel(F32Args p)
             constexpr int b = decltype(bc)::value;
             const int64_t m = m_base + b * 32;
             if (m < p.M) {
-                static_for<0, 8>([&](auto aq) {
+                static_for<0, 4 * TN>([&](auto aq) {
                     constexpr int a = decltype(aq)::value / 4, q = decltype(aq)::value % 4;
                     const int64_t n = n_base + a * 32 + q * 8;
                     store4_partial(part + m * p.N + n, p.N - n, vec, acc[a][b][4 * q + 0], acc[a][b][4 * q + 1],
@@ -228,7 +238,7 @@ f32_mfma_kernel(F32Args p)
             constexpr int b = decltype(bc)::value;
             const int64_t m = m_base + b * 32;
             if (m < p.M) {
-                static_for<0, 8>([&](auto aq) {
+                static_for<0, 4 * TN>([&](auto aq) {
                     constexpr int a = decltype(aq)::value / 4, q = decltype(aq)::value % 4;
                     const int64_t n = n_base + a * 32 + q * 8;
                     store4_epilogue(p.epi, m, n, p.N - n, vec, acc[a][b][4 * q + 0], acc[a][b][4 * q + 1],
@@ -254,10 +264,11 @@ hipError_t launch_f32_128x128(const Problem &p)
     const size_t lds = 2 * (size_t)F_STAGE;
     const bool ak = p.transA == 0, bk = p.transB == 1;
     void (*kern)(F32Args) = nullptr;
-    if (ak && bk) kern = f32_mfma_kernel<true, true>;
-    else if (ak && !bk) kern = f32_mfma_kernel<true, false>;
-    else if (!ak && bk) kern = f32_mfma_kernel<false, true>;
-    else kern = f32_mfma_kernel<false, false>;
+    constexpr int NW = 8;
+    if (ak && bk) kern = f32_mfma_kernel<true, true, NW>;
+    else if (ak && !bk) kern = f32_mfma_kernel<true, false, NW>;
+    else if (!ak && bk) kern = f32_mfma_kernel<false, true, NW>;
+    else kern = f32_mfma_kernel<false, false, NW>;
     static thread_local const void *configured[4] = {nullptr};
     bool done = false;
     for (const void *c : configured)
@@ -269,7 +280,7 @@ hipError_t launch_f32_128x128(const Problem &p)
         for (auto &c : configured)
             if (!c) { c = (const void *)kern; break; }
     }
-    hipLaunchKernelGGL(kern, grid, dim3(256), lds, p.stream, a);
+    hipLaunchKernelGGL(kern, grid, dim3(NW * 64), lds, p.stream, a);
     return hipGetLastError();
 }
 
