@@ -34,6 +34,8 @@ constexpr uint32_t PP_A_BYTES = PP_BM * BK * 2, PP_B_BYTES = PP_BN * BK * 2;
 constexpr uint32_t PP_SLOT = 32768;              // one half-block (A or B part of a k-block)
 constexpr int PP_SLOTS = 5;
 static_assert(PP_A_BYTES == PP_SLOT && PP_B_BYTES == PP_SLOT, "half-blocks are one slot each");
+typedef __attribute__((ext_vector_type(2))) uint32_t u32x2;
+typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
 constexpr int PP_EPI_LD = PP_WN + 4;            // floats per staged epilogue row (272 B: conflict-free)
 
 __device__ __forceinline__ void phase_sync()
@@ -236,6 +238,41 @@ __device__ __forceinline__ void pp_body(const Bf16Args &p)
     float *part = to_partial ? p.partial + (int64_t)blockIdx.y * p.M * p.N : nullptr;
     const bool vec = to_partial ? ((p.N & 3) == 0)
                                 : ((p.epi.ldc & 3) == 0 && (((uintptr_t)p.epi.C) & 15) == 0);
+    // Fast path for the common case (bf16 C, beta == 0, no bias / ReLU, aligned, no
+    // overhang in N): narrow in registers with v_cvt_pk_bf16_f32, stage bf16 (136-byte
+    // row pitch: conflict-free 64-bit writes), read back 16 bytes per lane and store
+    // 8 rows x 128 bytes per instruction.
+    const bool fast_bf16 = !to_partial && !p.epi.c_f32 && p.epi.beta == 0.0f && !p.epi.bias && !p.epi.relu &&
+                           (p.epi.ldc & 7) == 0 && (((uintptr_t)p.epi.C) & 15) == 0 && n0 + PP_BN <= p.N;
+    if (fast_bf16) {
+        LDS_AS char *stage_h = smem + (uint32_t)w * (32 * 136);
+        uint16_t *crow = (uint16_t *)p.epi.C + (m0 + wm * PP_WM) * p.epi.ldc + n0 + wn * PP_WN;
+        static_for<0, PP_TM>([&](auto bc) {
+            constexpr int b = decltype(bc)::value;
+            asm volatile("" ::: "memory");
+            static_for<0, PP_TN * 4>([&](auto aq) {
+                constexpr int a = decltype(aq)::value / 4, q = decltype(aq)::value % 4;
+                const int col = a * 32 + 8 * q + 4 * (lane >> 5);
+                const u32x2 pk = {pack_bf16x2(acc[a][b][4 * q + 0], acc[a][b][4 * q + 1]),
+                                  pack_bf16x2(acc[a][b][4 * q + 2], acc[a][b][4 * q + 3])};
+                *(LDS_AS u32x2 *)(stage_h + (lane & 31) * 136 + col * 2) = pk;
+            });
+            asm volatile("" ::: "memory");
+            __builtin_amdgcn_wave_barrier();
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const int idx = i * 64 + lane;
+                const int row = idx >> 3, c8 = idx & 7;
+                // 136-byte pitch keeps rows 8-byte aligned only: two 64-bit reads
+                const u32x2 lo = *(LDS_AS u32x2 *)(stage_h + row * 136 + c8 * 16);
+                const u32x2 hi = *(LDS_AS u32x2 *)(stage_h + row * 136 + c8 * 16 + 8);
+                if (m0 + wm * PP_WM + b * 32 + row < p.M)
+                    *(u32x4 *)(crow + (int64_t)(b * 32 + row) * p.epi.ldc + c8 * 8) = u32x4{lo[0], lo[1], hi[0], hi[1]};
+            }
+            __builtin_amdgcn_wave_barrier();
+        });
+        return;
+    }
     static_for<0, PP_TM>([&](auto bc) {
         constexpr int b = decltype(bc)::value;
         asm volatile("" ::: "memory");

@@ -314,8 +314,8 @@ __device__ __forceinline__ void store4_epilogue(const Epilogue &e, int64_t m, in
         *(f32x4 *)((float *)e.C + m * e.ldc + n) = f32x4{v0, v1, v2, v3};
     } else {
         uint2 out;
-        out.x = (uint32_t)f32_to_bf16_rne(v0) | ((uint32_t)f32_to_bf16_rne(v1) << 16);
-        out.y = (uint32_t)f32_to_bf16_rne(v2) | ((uint32_t)f32_to_bf16_rne(v3) << 16);
+        out.x = pack_bf16x2(v0, v1);
+        out.y = pack_bf16x2(v2, v3);
         *(uint2 *)((uint16_t *)e.C + m * e.ldc + n) = out;
     }
 }

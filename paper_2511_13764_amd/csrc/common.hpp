@@ -45,6 +45,16 @@ __device__ __forceinline__ uint16_t f32_to_bf16_rne(float f)
     return (uint16_t)(u >> 16);
 }
 
+// Two fp32 -> one register of two bf16 (first value in the low half) with the
+// hardware conversion v_cvt_pk_bf16_f32 (round to nearest even, NaN stays NaN).
+__device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi)
+{
+    typedef __attribute__((ext_vector_type(2))) float f32x2_t;
+    typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2_t;
+    const bf16x2_t r = __builtin_convertvector(f32x2_t{lo, hi}, bf16x2_t);
+    return __builtin_bit_cast(uint32_t, r);
+}
+
 __device__ __forceinline__ float bf16_to_f32(uint16_t h)
 {
     return __uint_as_float((uint32_t)h << 16);
