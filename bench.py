@@ -77,6 +77,18 @@ def main():
         wall = (time.perf_counter() - t0) / steps
         return wall, e0.elapsed_time(e1) * 1e-3 / steps
 
+    def per_launch(fn, n, group=1):
+        """Median and minimum HIP-event time of `n` samples of `group` launches each."""
+        evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(n)]
+        for a, b in evs:
+            a.record()
+            for _ in range(group):
+                fn()
+            b.record()
+        torch.cuda.synchronize()
+        ts = sorted(a.elapsed_time(b) * 1e-3 / group for a, b in evs)
+        return ts[len(ts) // 2], ts[0]
+
     # ------------------------------------------------------------------ headline: bf16 4096^3
     case = W.config3_bf16_square(4096)
     M, N, K = case.M, case.N, case.K
@@ -91,9 +103,29 @@ def main():
     wall, ev = time_launches(step, args.steps, args.warmup)
     variant = B.gemm_variant_name(B.gemm_last_variant())
     split = B.gemm_last_split()
+    med, mn = per_launch(step, 50)
     flops = 2.0 * M * N * K
     value = flops / wall / 1e12
     achieved = flops / ev / 1e12
+
+    # Matrix-pipe rate of this device with the same instruction and register shape but no
+    # LDS or memory traffic, on operands of the workload's distribution and on zeros: the
+    # rate is set by the chip's power management and depends on the operand values.
+    def mfma_rate(dtype, ops):
+        sink = torch.empty(2048 * 512, dtype=torch.float32, device="cuda")
+        fl = [0.0]
+
+        def probe():
+            fl[0] = B.gemm_mfma_probe(dtype, ops, 256, 2048, sink)
+        _, t = time_launches(probe, 20, 3)
+        return fl[0] / t / 1e12
+
+    g = torch.Generator(device="cuda").manual_seed(20251113)
+    ops_n = torch.randn(6 * 64 * 8, device="cuda", generator=g).to(torch.bfloat16)
+    measured = {"bf16_normal_operands": round(mfma_rate(B.DTYPE_BF16, ops_n), 1),
+                "bf16_zero_operands": round(mfma_rate(B.DTYPE_BF16, torch.zeros_like(ops_n)), 1),
+                "f32_uniform_operands": round(mfma_rate(B.DTYPE_F32, torch.rand(6 * 64, device="cuda", generator=g) * 2 - 1), 1),
+                "unit": "TFLOP/s", "what": "register-only MFMA issue loop, 2 waves per SIMD on every CU"}
 
     out = {
         "metric": METRIC, "value": round(value, 2), "unit": "TFLOP/s", "n_gpus": 1,
@@ -104,7 +136,10 @@ def main():
                    "variant": variant, "split": split},
         "roofline": {"bound": "mfma", "achieved": round(achieved, 2), "peak": PEAK_BF16, "unit": "TFLOP/s",
                      "frac": round(achieved / PEAK_BF16, 4), "traffic": None,
-                     "kernel": variant, "us_per_launch": round(ev * 1e6, 2)},
+                     "kernel": variant, "us_per_launch": round(ev * 1e6, 2),
+                     "us_median": round(med * 1e6, 2), "us_min": round(mn * 1e6, 2),
+                     "frac_of_measured_mfma_rate": round(achieved / measured["bf16_normal_operands"], 4)},
+        "measured_mfma_rate": measured,
     }
 
     # ------------------------------------------------------------------ CPU oracle beside it (bounded sample)
@@ -133,7 +168,9 @@ def main():
 
         def record(name, flops_, fn, peak, steps=50, warmup=5, bytes_=None):
             w_, e_ = time_launches(fn, steps, warmup)
-            r = {"us": round(e_ * 1e6, 2), "tflops": round(flops_ / e_ / 1e12, 2),
+            med_, min_ = per_launch(fn, 20, group=1 if e_ > 50e-6 else 20)
+            r = {"us": round(e_ * 1e6, 2), "us_median": round(med_ * 1e6, 2), "us_min": round(min_ * 1e6, 2),
+                 "tflops": round(flops_ / e_ / 1e12, 2),
                  "frac_mfma_peak": round(flops_ / e_ / 1e12 / peak, 4),
                  "variant": B.gemm_variant_name(B.gemm_last_variant()), "split": B.gemm_last_split()}
             if bytes_ is not None:
@@ -157,17 +194,28 @@ def main():
                    steps=20 if s == 8192 else 100)
             del a, b, c
         # MLP shapes, weights stored N x K
+        # The skinny cases are bound by the stream of the 90 MB weight matrix, which fits
+        # the 256 MB last-level cache: "warm" repeats one matrix, "cold" rotates over four
+        # (360 MB) so that every launch streams its weights from HBM.
         for which, (Kk, Nn) in (("up", (4096, 11008)), ("down", (11008, 4096))):
-            wgt = (torch.randn((Nn, Kk), device="cuda") * 0.02).to(torch.bfloat16)
+            wgts = [(torch.randn((Nn, Kk), device="cuda") * 0.02).to(torch.bfloat16) for _ in range(4)]
+            wgt = wgts[0]
             for Mm in (4096, 128, 16):
                 a = torch.randn((Mm, Kk), device="cuda").to(torch.bfloat16)
                 c = torch.empty((Mm, Nn), device="cuda", dtype=torch.bfloat16)
                 bytes_ = 2.0 * (Mm * Kk + Kk * Nn + Mm * Nn)
-                record(f"mlp_{which}_M{Mm}", 2.0 * Mm * Nn * Kk,
+                record(f"mlp_{which}_M{Mm}" + ("_warm" if Mm <= 128 else ""), 2.0 * Mm * Nn * Kk,
                        lambda: B.gemm_bf16(0, 1, Mm, Nn, Kk, a, Kk, wgt, Kk, 0.0, c, Nn, 0, workspace=ws),
                        PEAK_BF16, steps=30 if Mm == 4096 else 100, bytes_=bytes_ if Mm <= 128 else None)
+                if Mm <= 128:
+                    turn = [0]
+
+                    def cold():
+                        turn[0] = (turn[0] + 1) & 3
+                        B.gemm_bf16(0, 1, Mm, Nn, Kk, a, Kk, wgts[turn[0]], Kk, 0.0, c, Nn, 0, workspace=ws)
+                    record(f"mlp_{which}_M{Mm}_cold", 2.0 * Mm * Nn * Kk, cold, PEAK_BF16, steps=100, bytes_=bytes_)
                 del a, c
-            del wgt
+            del wgts, wgt
         # batch-reduce over scattered tiles
         c5 = W.config5_brgemm()
         pool = dev(c5.pool)

@@ -155,6 +155,23 @@ const char *gemm_variant_name(int v);
 int gemm_last_variant(void);
 int gemm_last_split(void);
 
+/*
+ * Measurement aid: the matrix-instruction rate of the device with no memory
+ * traffic, i.e. the ceiling of the multiply-accumulate step of Algorithm 1 (the
+ * hot loop) under the chip's own clock and power management.  Launches `blocks`
+ * workgroups of 8 wavefronts (two per SIMD, as the tuned kernels run); every
+ * wavefront issues `iters` x 8 independent 32x32 matrix instructions
+ * (bf16: 32x32x16, fp32: 32x32x2) on operands held in registers.
+ * operands: device, 6 x 64 lane values - 16 bytes (8 bf16) per lane for bf16,
+ * 4 bytes per lane for fp32; the first four blocks of 64 are A fragments, the
+ * last two B fragments.  Their values matter: the rate depends on them.
+ * sink: device, blocks * 512 floats, receives each lane's accumulator sum.
+ * flops (host, may be NULL): receives the number of floating-point operations
+ * of the launch.  Returns BRGEMM_OK, BRGEMM_INVALID_ARG or BRGEMM_HIP_ERROR.
+ */
+int gemm_mfma_probe(int dtype, const void *operands, int64_t iters, int blocks, float *sink,
+                    double *flops, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

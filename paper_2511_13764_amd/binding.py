@@ -28,7 +28,7 @@ EPI_NONE, EPI_BIAS, EPI_RELU = 0, 1, 2
 
 EXPORTS = ["gemm_f32", "gemm_bf16", "brgemm_bf16", "brgemm_fused", "gemm_workspace_bytes",
            "gemm_strerror", "gemm_last_hip_error", "gemm_force_variant", "gemm_variant_name",
-           "gemm_last_variant", "gemm_last_split"]
+           "gemm_last_variant", "gemm_last_split", "gemm_mfma_probe"]
 
 _lib = None
 
@@ -73,6 +73,8 @@ def load():
     lib.gemm_last_variant.argtypes = []
     lib.gemm_last_split.restype = ci
     lib.gemm_last_split.argtypes = []
+    lib.gemm_mfma_probe.restype = ci
+    lib.gemm_mfma_probe.argtypes = [ci, vp, i64, ci, vp, ctypes.POINTER(ctypes.c_double), vp]
     _lib = lib
     return lib
 
@@ -136,6 +138,15 @@ def brgemm_fused(in_dtype, transA, transB, M, N, K, batch, A_base, A_off, lda, B
                              _ptr(B_base), _ptr(B_off), ldb, beta, _ptr(C), ldc, int(bool(c_is_f32)),
                              _ptr(bias), epilogue, ws, nb, _stream(stream))
     return _check(rc, "brgemm_fused", check)
+
+
+def gemm_mfma_probe(dtype, operands, iters, blocks, sink, stream=None, check=True):
+    """Returns the number of floating-point operations of the launch."""
+    flops = ctypes.c_double(0.0)
+    rc = load().gemm_mfma_probe(dtype, _ptr(operands), iters, blocks, _ptr(sink), ctypes.byref(flops),
+                                _stream(stream))
+    _check(rc, "gemm_mfma_probe", check)
+    return flops.value
 
 
 def gemm_workspace_bytes(dtype, M, N, K, batch=1):

@@ -1,0 +1,95 @@
+// Register-only MFMA issue loop: the matrix-pipe rate of this chip under its own
+// clock and power management, with the operand values the caller supplies and no
+// LDS or memory traffic in the loop.  A measurement aid for the roofline of the
+// hot loop of Algorithm 1; not part of the product path.
+#include "../../include/brgemm.h"
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace {
+
+typedef __attribute__((ext_vector_type(8))) __bf16 pbf16x8;
+typedef __attribute__((ext_vector_type(16))) float pf32x16;
+
+// Same register shape as one wave of the tuned bf16 kernel: 4 A fragments, 2 B
+// fragments, 8 accumulators of 32x32; 8 independent MFMAs per iteration.
+__global__ void __launch_bounds__(512)
+probe_bf16_kernel(const uint16_t *ops, int64_t iters, float *sink)
+{
+    const int lane = threadIdx.x & 63;
+    pbf16x8 f[6];
+#pragma unroll
+    for (int q = 0; q < 6; ++q)
+        f[q] = *(const pbf16x8 *)(ops + ((size_t)q * 64 + lane) * 8);
+    pf32x16 acc[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i)
+#pragma unroll
+        for (int r = 0; r < 16; ++r)
+            acc[i][r] = 0.0f;
+    for (int64_t it = 0; it < iters; ++it) {
+#pragma unroll
+        for (int a = 0; a < 2; ++a)
+#pragma unroll
+            for (int b = 0; b < 4; ++b)
+                acc[a * 4 + b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f[4 + a], f[b], acc[a * 4 + b], 0, 0, 0);
+    }
+    float s = 0.0f;
+#pragma unroll
+    for (int i = 0; i < 8; ++i)
+#pragma unroll
+        for (int r = 0; r < 16; ++r)
+            s += acc[i][r];
+    sink[(size_t)blockIdx.x * 512 + threadIdx.x] = s;
+}
+
+// fp32: v_mfma_f32_32x32x2_f32, one float of A and of B per lane per instruction.
+__global__ void __launch_bounds__(512)
+probe_f32_kernel(const float *ops, int64_t iters, float *sink)
+{
+    const int lane = threadIdx.x & 63;
+    float f[6];
+#pragma unroll
+    for (int q = 0; q < 6; ++q)
+        f[q] = ops[q * 64 + lane];
+    pf32x16 acc[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i)
+#pragma unroll
+        for (int r = 0; r < 16; ++r)
+            acc[i][r] = 0.0f;
+    for (int64_t it = 0; it < iters; ++it) {
+#pragma unroll
+        for (int a = 0; a < 2; ++a)
+#pragma unroll
+            for (int b = 0; b < 4; ++b)
+                acc[a * 4 + b] = __builtin_amdgcn_mfma_f32_32x32x2f32(f[4 + a], f[b], acc[a * 4 + b], 0, 0, 0);
+    }
+    float s = 0.0f;
+#pragma unroll
+    for (int i = 0; i < 8; ++i)
+#pragma unroll
+        for (int r = 0; r < 16; ++r)
+            s += acc[i][r];
+    sink[(size_t)blockIdx.x * 512 + threadIdx.x] = s;
+}
+
+}  // namespace
+
+extern "C" int gemm_mfma_probe(int dtype, const void *operands, int64_t iters, int blocks, float *sink,
+                               double *flops, void *stream)
+{
+    if ((dtype != BRGEMM_DTYPE_F32 && dtype != BRGEMM_DTYPE_BF16) || !operands || !sink || iters < 0 ||
+        blocks <= 0 || blocks > (1 << 20))
+        return BRGEMM_INVALID_ARG;
+    const double per_mfma = dtype == BRGEMM_DTYPE_BF16 ? 2.0 * 32 * 32 * 16 : 2.0 * 32 * 32 * 2;
+    if (flops)
+        *flops = per_mfma * 8.0 * (double)iters * 8.0 * (double)blocks;   // 8 MFMAs x 8 waves
+    if (dtype == BRGEMM_DTYPE_BF16)
+        probe_bf16_kernel<<<dim3((unsigned)blocks), dim3(512), 0, (hipStream_t)stream>>>(
+            (const uint16_t *)operands, iters, sink);
+    else
+        probe_f32_kernel<<<dim3((unsigned)blocks), dim3(512), 0, (hipStream_t)stream>>>(
+            (const float *)operands, iters, sink);
+    return hipGetLastError() == hipSuccess ? BRGEMM_OK : BRGEMM_HIP_ERROR;
+}
