@@ -201,38 +201,7 @@ bf16_mfma_kernel(Bf16Args p)
     // ---- epilogue: beta*C, bias, ReLU, narrowing, store (or raw partial for a split)
     // Every accumulator index below is a compile-time constant (static_for), so the
     // tile never leaves the register file.
-    const int64_t m_base = m0 + wm * WM + (lane & 31);
-    const int64_t n_base = n0 + wn * WN + 4 * (lane >> 5);
-    if (p.split > 1) {
-        float *part = p.partial + (int64_t)blockIdx.y * p.M * p.N;
-        const bool vec = (p.N & 3) == 0;
-        static_for<0, TM>([&](auto bc) {
-            constexpr int b = decltype(bc)::value;
-            const int64_t m = m_base + b * 32;
-            if (m < p.M) {
-                static_for<0, TN * 4>([&](auto aq) {
-                    constexpr int a = decltype(aq)::value / 4, q = decltype(aq)::value % 4;
-                    const int64_t n = n_base + a * 32 + q * 8;
-                    store4_partial(part + m * p.N + n, p.N - n, vec, acc[a][b][4 * q + 0], acc[a][b][4 * q + 1],
-                                   acc[a][b][4 * q + 2], acc[a][b][4 * q + 3]);
-                });
-            }
-        });
-    } else {
-        const bool vec = (p.epi.ldc & 3) == 0 && (((uintptr_t)p.epi.C) & 15) == 0;
-        static_for<0, TM>([&](auto bc) {
-            constexpr int b = decltype(bc)::value;
-            const int64_t m = m_base + b * 32;
-            if (m < p.M) {
-                static_for<0, TN * 4>([&](auto aq) {
-                    constexpr int a = decltype(aq)::value / 4, q = decltype(aq)::value % 4;
-                    const int64_t n = n_base + a * 32 + q * 8;
-                    store4_epilogue(p.epi, m, n, p.N - n, vec, acc[a][b][4 * q + 0], acc[a][b][4 * q + 1],
-                                    acc[a][b][4 * q + 2], acc[a][b][4 * q + 3]);
-                });
-            }
-        });
-    }
+    store_wave_tile<TM, TN>(p, acc, m0 + wm * WM + (lane & 31), n0 + wn * WN + 4 * (lane >> 5), (int)blockIdx.y);
 }
 
 // ---------------------------------------------------------------------------

@@ -1,0 +1,185 @@
+// bf16 GEMM kernel for few rows of A (skinny M: the M = 16 / 128 shapes of an MLP
+// layer), where the time goes into streaming the B matrix from HBM once, not into the
+// matrix pipe - the regime the paper describes as bound by memory bandwidth
+// (Section 6, discussion of the flat-layout results).
+//
+// A workgroup of 4 wavefronts owns a BM x 128 block of C (BM = 32, 64 or 128) and
+// walks its share of K in 64-deep blocks.  What matters here is how many bytes are
+// in flight per CU, so the LDS is a ring of three stages, each holding one k-block
+// of A and B: the loads for block t + 2 are requested while block t is multiplied,
+// and the small footprint (60 to 96 KiB) lets a second workgroup share the CU.
+// (Sweeps of 2 to 8 stages on the MLP shapes: three is best or within 3 % of the
+// best everywhere; deeper rings lose the second workgroup and gain nothing.)
+// Loads are global->LDS DMA (no register staging), counted per wave with vmcnt:
+// before block t is read a wave waits until only the loads of block t + 1 are
+// outstanding, then one workgroup barrier publishes the block and frees the slot
+// read in the previous iteration.
+#include "bf16_tiles.hpp"
+
+namespace brg {
+
+namespace {
+
+constexpr int ST_BN = 128;
+constexpr int ST_STAGES = 3;
+
+template <int BM, bool B_KMAJ>
+__global__ void __launch_bounds__(256)
+bf16_stream_kernel(Bf16Args p)
+{
+    typedef KMajorTile<BM, 4> ATile;
+    typedef typename TileOf<ST_BN, 4, B_KMAJ>::type BTile;
+    constexpr int WGM = BM == 128 ? 2 : 1, WGN = 4 / WGM;     // wave grid
+    constexpr int WM = BM / WGM, WN = ST_BN / WGN;
+    constexpr int TM = WM / 32, TN = WN / 32;
+    constexpr uint32_t A_BYTES = BM * BK * 2, B_BYTES = ST_BN * BK * 2;
+    constexpr uint32_t STAGE = A_BYTES + B_BYTES;
+    constexpr int L = ATile::kPerWave + BTile::kPerWave;        // loads per wave per block
+    constexpr int stages = ST_STAGES;
+    static_assert((ST_STAGES - 2) * L <= 63, "outstanding loads must fit vmcnt");
+
+    extern __shared__ __attribute__((aligned(1024))) char smem_generic[];
+    LDS_AS char *smem = (LDS_AS char *)smem_generic;
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wm = w / WGN, wn = w % WGN;
+
+    const int tm = (int)blockIdx.x % p.tiles_m, tn = (int)blockIdx.x / p.tiles_m;
+    const int64_t m0 = (int64_t)tm * BM, n0 = (int64_t)tn * ST_BN;
+
+    const int kblocks = (int)(p.K / BK);
+    const int per = (kblocks + p.split - 1) / p.split;
+    const int it_begin = (int)blockIdx.y * per;
+    const int it_end = (it_begin + per < kblocks) ? it_begin + per : kblocks;
+    const int n_iter = it_end > it_begin ? it_end - it_begin : 0;
+
+    // Rows / columns past the edge of the matrix are redirected to a valid one (their
+    // products land in accumulator rows / columns that are never stored), so every
+    // wave issues exactly L loads per block and the vmcnt arithmetic below holds.
+    uint32_t a_src[ATile::kPerWave], b_src[BTile::kPerWave];
+#pragma unroll
+    for (int j = 0; j < ATile::kPerWave; ++j)
+        a_src[j] = ATile::src_rel_bytes(w, j, lane, m0, p.M, p.lda);
+#pragma unroll
+    for (int j = 0; j < BTile::kPerWave; ++j)
+        b_src[j] = BTile::src_rel_bytes(w, j, lane, n0, p.N, p.ldb);
+    const int64_t b_kstep = B_KMAJ ? (int64_t)BK : (int64_t)BK * p.ldb;
+    const uint16_t *ld_a = uniform_ptr(p.A + m0 * p.lda + (int64_t)it_begin * BK);
+    const uint16_t *ld_b = uniform_ptr(p.B + (B_KMAJ ? n0 * p.ldb : n0) + (int64_t)it_begin * b_kstep);
+    int ld_slot = 0;
+
+    auto issue_loads = [&]() {
+        const uint32_t base = (uint32_t)ld_slot * STAGE;
+#pragma unroll
+        for (int j = 0; j < BTile::kPerWave; ++j)
+            load16_to_lds_saddr((const char *)ld_b, b_src[j],
+                                (uint32_t)(size_t)(smem + base + A_BYTES + BTile::dst_byte(w, j)));
+#pragma unroll
+        for (int j = 0; j < ATile::kPerWave; ++j)
+            load16_to_lds_saddr((const char *)ld_a, a_src[j], (uint32_t)(size_t)(smem + base + ATile::dst_byte(w, j)));
+        ld_a += BK;
+        ld_b += b_kstep;
+        ld_slot = ld_slot + 1 == stages ? 0 : ld_slot + 1;
+    };
+    f32x16 acc[TN][TM];
+#pragma unroll
+    for (int a = 0; a < TN; ++a)
+#pragma unroll
+        for (int b = 0; b < TM; ++b)
+#pragma unroll
+            for (int r = 0; r < 16; ++r)
+                acc[a][b][r] = 0.0f;
+
+    const int ahead = stages - 1;
+    for (int s = 0; s < ahead && s < n_iter; ++s)
+        issue_loads();
+
+    int rd_slot = 0;
+    for (int t = 0; t < n_iter; ++t) {
+        // Block t has landed once only the stages - 2 younger blocks are outstanding.
+        if (t + stages - 2 < n_iter)
+            wait_vmcnt_le<(ST_STAGES - 2) * L>();
+        else
+            wait_vmcnt0();                          // tail: fewer blocks than slots remain
+        block_sync();
+        if (t + ahead < n_iter)
+            issue_loads();                          // into the slot read in iteration t - 1
+        LDS_AS char *at = smem + (uint32_t)rd_slot * STAGE;
+        LDS_AS char *bt = at + A_BYTES;
+        bf16x8 fa[4][TM], fb[4][TN];
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks) {
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+                fa[ks][i] = ATile::read_frag(at, wm * WM, i, ks, lane);
+#pragma unroll
+            for (int i = 0; i < TN; ++i)
+                fb[ks][i] = BTile::read_frag(bt, wn * WN, i, ks, lane);
+        }
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks)
+#pragma unroll
+            for (int a = 0; a < TN; ++a)
+#pragma unroll
+                for (int b = 0; b < TM; ++b)
+                    acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[ks][a], fa[ks][b], acc[a][b], 0, 0, 0);
+        // The fragments are in registers before the next barrier lets another wave's
+        // loads overwrite this slot.
+        wait_lgkmcnt0();
+        rd_slot = rd_slot + 1 == stages ? 0 : rd_slot + 1;
+    }
+
+    store_wave_tile<TM, TN>(p, acc, m0 + wm * WM + (lane & 31), n0 + wn * WN + 4 * (lane >> 5), (int)blockIdx.y);
+}
+
+template <int BM>
+hipError_t launch_stream(const Problem &p)
+{
+    Bf16Args a;
+    a.M = p.M; a.N = p.N; a.K = p.K; a.batch = 1;
+    a.A = (const uint16_t *)p.A; a.A_off = nullptr; a.lda = p.lda;
+    a.B = (const uint16_t *)p.B; a.B_off = nullptr; a.ldb = p.ldb;
+    a.epi.beta = p.beta; a.epi.C = p.C; a.epi.ldc = p.ldc; a.epi.c_f32 = p.c_f32;
+    a.epi.bias = p.bias; a.epi.relu = p.relu;
+    a.split = p.split; a.partial = p.partial;
+    a.tiles_m = (int)((p.M + BM - 1) / BM);
+    a.tiles_n = (int)((p.N + ST_BN - 1) / ST_BN);
+    const dim3 grid((unsigned)(a.tiles_m * a.tiles_n), (unsigned)p.split);
+    const size_t lds = (size_t)ST_STAGES * (BM + ST_BN) * BK * 2;
+    void (*kern)(Bf16Args) = p.transB == 1 ? bf16_stream_kernel<BM, true> : bf16_stream_kernel<BM, false>;
+    static thread_local const void *configured[2] = {nullptr};
+    bool done = false;
+    for (const void *c : configured)
+        done = done || c == (const void *)kern;
+    if (!done) {
+        hipError_t e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e != hipSuccess)
+            return e;
+        for (auto &c : configured)
+            if (!c) { c = (const void *)kern; break; }
+    }
+    hipLaunchKernelGGL(kern, grid, dim3(256), lds, p.stream, a);
+    return hipGetLastError();
+}
+
+}  // namespace
+
+hipError_t launch_bf16_stream(const Problem &p, int bm)
+{
+    switch (bm) {
+    case 32: return launch_stream<32>(p);
+    case 64: return launch_stream<64>(p);
+    case 128: return launch_stream<128>(p);
+    default: return hipErrorInvalidValue;
+    }
+}
+
+// Plain GEMM with A stored M x K (k contiguous); B in either order.
+bool bf16_stream_eligible(const Problem &p)
+{
+    return bf16_mfma_eligible(p) && p.transA == 0 && p.batch == 1 && !p.A_off && !p.B_off;
+}
+
+}  // namespace brg

@@ -37,6 +37,25 @@ struct Bf16Args {
 __device__ __forceinline__ void wait_vmcnt0() { __builtin_amdgcn_s_waitcnt(0x0F70); }
 __device__ __forceinline__ void wait_lgkmcnt0() { __builtin_amdgcn_s_waitcnt(0xC07F); }
 __device__ __forceinline__ void wait_vmcnt8() { __builtin_amdgcn_s_waitcnt(0x0F78); }
+// Wait until at most N vector-memory loads of this wave are outstanding (N <= 63).
+template <int N>
+__device__ __forceinline__ void wait_vmcnt_le()
+{
+    static_assert(N >= 0 && N <= 63, "vmcnt is a 6-bit counter");
+    __builtin_amdgcn_s_waitcnt(0x0F70 | (N & 15) | ((N >> 4) << 14));
+}
+
+// Workgroup barrier that neither the compiler's scheduler nor its memory-operation
+// motion may cross.  Unlike __syncthreads() it emits no wait of its own: callers wait
+// for exactly the loads and LDS reads that must be complete.
+__device__ __forceinline__ void block_sync()
+{
+    __builtin_amdgcn_sched_barrier(0);
+    asm volatile("" ::: "memory");
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
+    __builtin_amdgcn_sched_barrier(0);
+}
 
 // Tell the compiler a pointer is wave-uniform (keeps it in SGPRs).
 __device__ __forceinline__ const uint16_t *uniform_ptr(const uint16_t *p)
@@ -317,6 +336,46 @@ __device__ __forceinline__ void store4_epilogue(const Epilogue &e, int64_t m, in
         out.x = pack_bf16x2(v0, v1);
         out.y = pack_bf16x2(v2, v3);
         *(uint2 *)((uint16_t *)e.C + m * e.ldc + n) = out;
+    }
+}
+
+// Store one wave's register tile (TN x TM accumulators of 32x32, computed with the
+// operands swapped so that lane l owns row l%32 and 4 consecutive columns per group
+// of 4 registers): raw fp32 partial sums for a split reduction, else the epilogue.
+// m_base / n_base: the row / first column this lane owns in accumulator (0, 0).
+template <int TM, int TN>
+__device__ __forceinline__ void store_wave_tile(const Bf16Args &p, f32x16 (&acc)[TN][TM], int64_t m_base,
+                                                int64_t n_base, int split_index)
+{
+    if (p.split > 1) {
+        float *part = p.partial + (int64_t)split_index * p.M * p.N;
+        const bool vec = (p.N & 3) == 0;
+        static_for<0, TM>([&](auto bc) {
+            constexpr int b = decltype(bc)::value;
+            const int64_t m = m_base + b * 32;
+            if (m < p.M) {
+                static_for<0, TN * 4>([&](auto aq) {
+                    constexpr int a = decltype(aq)::value / 4, q = decltype(aq)::value % 4;
+                    const int64_t n = n_base + a * 32 + q * 8;
+                    store4_partial(part + m * p.N + n, p.N - n, vec, acc[a][b][4 * q + 0], acc[a][b][4 * q + 1],
+                                   acc[a][b][4 * q + 2], acc[a][b][4 * q + 3]);
+                });
+            }
+        });
+    } else {
+        const bool vec = (p.epi.ldc & 3) == 0 && (((uintptr_t)p.epi.C) & 15) == 0;
+        static_for<0, TM>([&](auto bc) {
+            constexpr int b = decltype(bc)::value;
+            const int64_t m = m_base + b * 32;
+            if (m < p.M) {
+                static_for<0, TN * 4>([&](auto aq) {
+                    constexpr int a = decltype(aq)::value / 4, q = decltype(aq)::value % 4;
+                    const int64_t n = n_base + a * 32 + q * 8;
+                    store4_epilogue(p.epi, m, n, p.N - n, vec, acc[a][b][4 * q + 0], acc[a][b][4 * q + 1],
+                                    acc[a][b][4 * q + 2], acc[a][b][4 * q + 3]);
+                });
+            }
+        });
     }
 }
 

@@ -12,6 +12,9 @@ const char *variant_name(int v)
     case V_BF16_128x128: return "bf16_128x128x64";
     case V_BF16_PP256: return "bf16_pingpong_256x256x64";
     case V_F32_128x128: return "f32_128x128x32";
+    case V_BF16_STREAM32: return "bf16_stream_32x128x64";
+    case V_BF16_STREAM64: return "bf16_stream_64x128x64";
+    case V_BF16_STREAM128: return "bf16_stream_128x128x64";
     default: return "";
     }
 }
@@ -24,6 +27,9 @@ bool variant_eligible(int v, const Problem &p)
     case V_BF16_128x128: return bf16_mfma_eligible(p);
     case V_BF16_PP256: return bf16_pingpong_eligible(p);
     case V_F32_128x128: return f32_mfma_eligible(p);
+    case V_BF16_STREAM32:
+    case V_BF16_STREAM64:
+    case V_BF16_STREAM128: return bf16_stream_eligible(p);
     default: return false;
     }
 }
@@ -67,10 +73,40 @@ static int split_for_small_grid(const Problem &p, size_t workspace_bytes)
     return best;
 }
 
+// Reduction split for the skinny-M streaming kernels (BM x 128 tiles).  Split sweeps
+// on the MLP shapes show the time following rounds * (k-blocks per workgroup), where
+// rounds = workgroups / 256 rounded up (a CU works through its workgroups at a fixed
+// rate), plus a cost per split for the partial tiles that grows with BM.
+static int split_for_stream(const Problem &p, int bm, size_t workspace_bytes)
+{
+    const int64_t tiles = ((p.M + bm - 1) / bm) * ((p.N + 127) / 128);
+    const int64_t kblocks = p.K / 64;
+    const double per_split = 0.75 * bm / 32.0;
+    int best = 1;
+    double best_cost = 1e30;
+    for (int s = 1; s <= kMaxSplit; ++s) {
+        const int64_t per = (kblocks + s - 1) / s;
+        if (s > 1 && (per < 8 || split_bytes(p, s) > workspace_bytes))
+            continue;
+        const double rounds = (double)((tiles * s + 255) / 256);
+        const double cost = rounds * (double)per + per_split * s;
+        if (cost < best_cost) {
+            best_cost = cost;
+            best = s;
+        }
+    }
+    return best;
+}
+
 int choose_plan(const Problem &p, size_t workspace_bytes, int forced_variant, int forced_split, Plan *out)
 {
     Plan plan{V_GENERIC, 1};
-    if (bf16_mfma_eligible(p)) {
+    if (p.M <= 128 && bf16_stream_eligible(p)) {
+        // Few rows of A: the time goes into streaming B once.
+        const int bm = p.M <= 32 ? 32 : p.M <= 64 ? 64 : 128;
+        plan.variant = bm == 32 ? V_BF16_STREAM32 : bm == 64 ? V_BF16_STREAM64 : V_BF16_STREAM128;
+        plan.split = split_for_stream(p, bm, workspace_bytes);
+    } else if (bf16_mfma_eligible(p)) {
         // 256x256 tiles once they can occupy most of the 256 CUs, else 128x128, whose
         // workgroups fit two to a CU.
         const int64_t t256 = ((p.M + 255) / 256) * ((p.N + 255) / 256);
@@ -105,6 +141,9 @@ hipError_t launch_variant(int v, const Problem &p)
     case V_BF16_128x128: return launch_bf16_128x128(p);
     case V_BF16_PP256: return launch_bf16_pingpong(p);
     case V_F32_128x128: return launch_f32_128x128(p);
+    case V_BF16_STREAM32: return launch_bf16_stream(p, 32);
+    case V_BF16_STREAM64: return launch_bf16_stream(p, 64);
+    case V_BF16_STREAM128: return launch_bf16_stream(p, 128);
     default: return hipErrorInvalidValue;
     }
 }

@@ -12,6 +12,9 @@ enum Variant {
     V_BF16_128x128,     // bf16, 128x128x64 workgroup tile, 64x64 wave tile
     V_BF16_PP256,       // bf16, 256x256x64 tile, 8 waves in alternating memory/compute phases
     V_F32_128x128,      // fp32, 128x128x32 tile, fp32 MFMA
+    V_BF16_STREAM32,    // bf16, skinny M: 32x128x64 tile, deep LDS ring (HBM-bound shapes)
+    V_BF16_STREAM64,    // bf16, skinny M: 64x128x64 tile, deep LDS ring
+    V_BF16_STREAM128,   // bf16, skinny M: 128x128x64 tile, deep LDS ring
     V_COUNT
 };
 
@@ -43,5 +46,9 @@ hipError_t launch_f32_128x128(const Problem &p);
 // bf16_pingpong.hip
 bool bf16_pingpong_eligible(const Problem &p);
 hipError_t launch_bf16_pingpong(const Problem &p);
+
+// bf16_stream.hip
+bool bf16_stream_eligible(const Problem &p);
+hipError_t launch_bf16_stream(const Problem &p, int bm);
 
 }  // namespace brg

@@ -115,3 +115,13 @@ def test_workspace_rules(lib):
         B.gemm_force_variant(-1, 0)
     with pytest.raises(B.BrgemmError):
         B.gemm_force_variant(10_000, 0)
+
+
+def test_mfma_probe_rejects_bad_arguments(lib):
+    for kw in (dict(dtype=7), dict(operands=0), dict(sink=0), dict(iters=-1), dict(blocks=0)):
+        a = dict(dtype=B.DTYPE_BF16, operands=P, iters=1, blocks=1, sink=P)
+        a.update(kw)
+        rc = B.gemm_mfma_probe(a["dtype"], a["operands"], a["iters"], a["blocks"], a["sink"], stream=0, check=False)
+        assert rc == 0.0        # rejected before launch: no operation count is reported
+        assert lib.gemm_mfma_probe(a["dtype"], a["operands"], a["iters"], a["blocks"], a["sink"], None, 0) == \
+            B.INVALID_ARG

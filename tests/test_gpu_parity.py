@@ -334,3 +334,50 @@ def test_every_variant_on_an_aligned_problem(oracle):
                         assert e.code == B.INVALID_ARG      # variant does not take this dtype / layout
                         continue
                     assert H.rel_fro(H.widen(out), ref) <= 1e-5, (name, split)
+
+
+@pytest.mark.gpu
+def test_mfma_probe_counts_what_it_claims():
+    """The register-only issue loop really executes iters x 8 matrix instructions per
+    wave: with all-ones operands every accumulator element grows by the reduction
+    depth (16 for bf16, 2 for fp32) per instruction."""
+    iters, blocks = 37, 5
+    sink = torch.empty(blocks * 512, dtype=torch.float32, device="cuda")
+    ones_h = torch.ones(6 * 64 * 8, device="cuda").to(torch.bfloat16)
+    fl = B.gemm_mfma_probe(B.DTYPE_BF16, ones_h, iters, blocks, sink)
+    assert fl == 2.0 * 32 * 32 * 16 * 8 * iters * 8 * blocks
+    assert (sink.cpu().numpy() == 8 * 16 * iters * 16).all()
+    ones_f = torch.ones(6 * 64, device="cuda")
+    fl = B.gemm_mfma_probe(B.DTYPE_F32, ones_f, iters, blocks, sink)
+    assert fl == 2.0 * 32 * 32 * 2 * 8 * iters * 8 * blocks
+    assert (sink.cpu().numpy() == 8 * 16 * iters * 2).all()
+
+
+@pytest.mark.gpu
+@pytest.mark.parametrize("tB", [0, 1])
+@pytest.mark.parametrize("M,N,K", [(16, 200, 1024), (100, 392, 640), (33, 128, 64), (128, 264, 2048), (1, 8, 192)])
+def test_stream_variants_ragged_edges_and_splits(oracle, M, N, K, tB):
+    """The skinny-M streaming kernels, each forced in turn, on shapes whose M and N end
+    inside a tile, with padded leading dimensions (NaN in the padding), beta != 0, a
+    ring longer and shorter than the k-block count, and with and without a split."""
+    pad = 8
+    rb, cb = (N, K) if tB else (K, N)
+    A = np.full((M, K + pad), np.nan, np.float32)
+    Bm = np.full((rb, cb + pad), np.nan, np.float32)
+    A[:, :K] = W.normal_f32(71, 0, (M, K))
+    Bm[:, :cb] = W.normal_f32(71, 1, (rb, cb))
+    # fp32 C: the comparison then sees the kernel's own error only (a bf16 C of a few
+    # elements can exceed the bf16 tolerance by rounding alone); bf16 C is covered by
+    # the MLP-shape tests, which take these kernels automatically.
+    C0 = W.normal_f32(71, 2, (M, N))
+    case = W.GemmCase(f"stream_{M}x{N}x{K}_t0{tB}", "bf16", M, N, K, 0, tB, 0.5,
+                      W.to_bf16_bits(A), W.to_bf16_bits(Bm), C0, True)
+    ref = H.oracle_gemm_case(oracle, case)
+    names = B.variants()
+    ws = B.gemm_workspace_bytes(1, M, N, K)
+    for name in ("bf16_stream_32x128x64", "bf16_stream_64x128x64", "bf16_stream_128x128x64"):
+        for split in (1, 3):
+            say(f"{case.name} variant={name} split={split}")
+            out, _ = H.run_gemm_case(case, ldc=N + pad, workspace_bytes=ws, force=(names.index(name), split))
+            assert np.isfinite(H.widen(out)).all(), "padding (NaN) leaked into the result"
+            assert H.rel_fro(H.widen(out), ref) <= H.TOL_BF16_F32OUT, (name, split)
