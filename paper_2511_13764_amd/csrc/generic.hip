@@ -9,7 +9,7 @@
 // bias / ReLU / narrowing once at the end.  bf16 inputs are widened exactly to
 // fp32 when they are staged into LDS, so each product is exact in fp32 and the
 // sum is fp32 (the appendix listings: widen, multiply, add in f32).
-#include "common.hpp"
+#include "bf16_tiles.hpp"
 
 namespace brg {
 
@@ -120,6 +120,25 @@ reduce_kernel(int64_t M, int64_t N, int split, const float *partial, Epilogue ep
     }
 }
 
+// The same sum, four consecutive columns per thread with 16-byte reads of the
+// partial tiles (N a multiple of 4; C 16-byte aligned with ldc a multiple of 4).
+// The slices are added in the order 0, 1, ..., split - 1, as in the scalar kernel.
+__global__ void __launch_bounds__(256)
+reduce4_kernel(int M, int quads_per_row, int split, const float *partial, Epilogue epi)
+{
+    const int q = (int)blockIdx.x * 256 + (int)threadIdx.x;
+    const int m = (int)blockIdx.y;
+    if (q >= quads_per_row)
+        return;
+    const int64_t N = (int64_t)quads_per_row * 4;
+    const int64_t total = (int64_t)M * N;
+    const float *src = partial + (int64_t)m * N + (int64_t)q * 4;
+    f32x4 s = *(const f32x4 *)src;
+    for (int z = 1; z < split; ++z)
+        s += *(const f32x4 *)(src + (int64_t)z * total);
+    store4_epilogue(epi, m, (int64_t)q * 4, 4, true, s[0], s[1], s[2], s[3]);
+}
+
 __global__ void __launch_bounds__(256)
 scale_only_kernel(int64_t M, int64_t N, Epilogue epi)
 {
@@ -165,6 +184,12 @@ static unsigned elementwise_grid(int64_t total)
 
 hipError_t launch_reduce(const Problem &p)
 {
+    if ((p.N & 3) == 0 && (p.ldc & 3) == 0 && (((uintptr_t)p.C) & 15) == 0 && p.M <= 65535) {
+        const int quads = (int)(p.N / 4);
+        hipLaunchKernelGGL(reduce4_kernel, dim3((unsigned)((quads + 255) / 256), (unsigned)p.M), dim3(256), 0,
+                           p.stream, (int)p.M, quads, p.split, p.partial, make_epilogue(p));
+        return hipGetLastError();
+    }
     hipLaunchKernelGGL(reduce_kernel, dim3(elementwise_grid(p.M * p.N)), dim3(256), 0, p.stream, p.M, p.N,
                        p.split, p.partial, make_epilogue(p));
     return hipGetLastError();
