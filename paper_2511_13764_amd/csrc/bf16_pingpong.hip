@@ -213,7 +213,9 @@ __device__ __forceinline__ void pp_body(const Bf16Args &p)
             if (group == 1) {
                 // A(t+1), requested one block ago, must have landed before the barrier
                 // that precedes its first read; the 8 loads just issued may still fly.
-                if (request)
+                // Counting is only valid when all 8 loads were really issued: on an edge
+                // tile a wave-load whose lanes are all switched off is skipped entirely.
+                if (request && !EDGE)
                     wait_vmcnt8();
                 else
                     wait_vmcnt0();

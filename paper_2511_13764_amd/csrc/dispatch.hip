@@ -98,6 +98,32 @@ static int split_for_stream(const Problem &p, int bm, size_t workspace_bytes)
     return best;
 }
 
+// Reduction split for the fp32 kernel when its 128x128 tiles cannot fill the chip.
+// Time model in microseconds, fitted to split sweeps (256^3 ... 2048^3 and the skinny
+// MLP shape): one workgroup per CU works through a 128x128x32 k-block in ~2.0 us
+// (the fp32 MFMA rate), a launch costs ~8 us of latency, and the reduction adds a
+// second launch plus split*M*N*8 bytes at ~3 TB/s.
+static int split_for_f32(const Problem &p, size_t workspace_bytes)
+{
+    const int64_t tiles = ((p.M + 127) / 128) * ((p.N + 127) / 128);
+    const int64_t kblocks = p.K / 32;
+    int best = 1;
+    double best_t = 1e30;
+    for (int s = 1; s <= kMaxSplit; ++s) {
+        if (s > 1 && (kblocks / s < 1 || split_bytes(p, s) > workspace_bytes))
+            continue;
+        const double rounds = (double)((tiles * s + 255) / 256);
+        const double per = (double)((kblocks + s - 1) / s);
+        const double t_reduce = s > 1 ? 4.0 + (double)s * (double)p.M * (double)p.N * 8.0 / 3.0e6 : 0.0;
+        const double t = 8.0 + rounds * per * 2.0 + t_reduce;
+        if (t < best_t * 0.97) {
+            best_t = t;
+            best = s;
+        }
+    }
+    return best;
+}
+
 int choose_plan(const Problem &p, size_t workspace_bytes, int forced_variant, int forced_split, Plan *out)
 {
     Plan plan{V_GENERIC, 1};
@@ -107,18 +133,20 @@ int choose_plan(const Problem &p, size_t workspace_bytes, int forced_variant, in
         plan.variant = bm == 32 ? V_BF16_STREAM32 : bm == 64 ? V_BF16_STREAM64 : V_BF16_STREAM128;
         plan.split = split_for_stream(p, bm, workspace_bytes);
     } else if (bf16_mfma_eligible(p)) {
-        // 256x256 tiles once they can occupy most of the 256 CUs, else 128x128, whose
-        // workgroups fit two to a CU.
-        const int64_t t256 = ((p.M + 255) / 256) * ((p.N + 255) / 256);
-        if (t256 >= 160) {
+        // 128x128 tiles while all of them are resident at once (two workgroups per CU:
+        // 512), 256x256 tiles beyond that (measured crossover on squares: 2816 -> 3072).
+        const int64_t t128 = ((p.M + 127) / 128) * ((p.N + 127) / 128);
+        if (t128 > 512) {
             plan.variant = bf16_pingpong_eligible(p) ? V_BF16_PP256 : V_BF16_256x256;
         } else {
             plan.variant = V_BF16_128x128;
             plan.split = split_for_small_grid(p, workspace_bytes);
         }
     }
-    if (f32_mfma_eligible(p))
+    if (f32_mfma_eligible(p)) {
         plan.variant = V_F32_128x128;
+        plan.split = split_for_f32(p, workspace_bytes);
+    }
     if (forced_variant >= 0) {
         if (forced_variant >= V_COUNT || !variant_eligible(forced_variant, p))
             return BRGEMM_INVALID_ARG;

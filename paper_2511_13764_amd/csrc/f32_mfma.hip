@@ -6,8 +6,9 @@
 //
 // fp32 MFMA runs at 1/16 of the bf16 rate, so per k-block the 64 MFMAs of a SIMD
 // take ~4096 cycles against 32 KiB of loads and ~100 KiB of LDS reads per CU: the
-// kernel is bound by the matrix pipe and a two-stage LDS pipeline is enough; two
-// waves per SIMD cover each other's load issue and LDS latency.  Global -> LDS copies
+// kernel is bound by the matrix pipe; two waves per SIMD cover each other's load
+// issue and LDS latency, and a three-stage LDS ring gives every load a whole k-block
+// of time to land.  Global -> LDS copies
 // use the scalar-base form of global_load_lds_dwordx4, spread between the MFMA groups.
 //
 // LDS images.  An operand whose contiguous direction is k keeps 128-byte rows with
@@ -181,72 +182,102 @@ f32_mfma_kernel(F32Args p)
                     acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x2f32(fb[buf][a][e], fa[buf][b][e], acc[a][b], 0, 0, 0);
     };
 
+    // Three LDS stages: while block `it` is multiplied the loads of block it + 2 are
+    // issued (a quarter after each group of MFMAs) into the stage that block it - 1
+    // occupied, and the barrier that ends the block only waits for block it + 1, which
+    // was requested a whole block (~4000 cycles) earlier.
+    // Counting outstanding loads is only valid when every load is really issued: on a
+    // tile that overhangs the matrix a wave-load whose lanes are all switched off is
+    // skipped, so such tiles wait for everything instead.
+    constexpr int L = 2 * PER_OP;               // loads per wave per block
+    const bool counted = m0 + FB <= p.M && n0 + FB <= p.N;
     if (n_iter > 0) {
 #pragma unroll
-        for (int q = 0; q < 2 * PER_OP; ++q)
+        for (int q = 0; q < L; ++q)
             issue_one(0, q);
         advance();
-        wait_vmcnt0();
-        __syncthreads();
+        if (n_iter > 1) {
+#pragma unroll
+            for (int q = 0; q < L; ++q)
+                issue_one(1, q);
+            advance();
+            if (counted)
+                wait_vmcnt_le<L>();
+            else
+                wait_vmcnt0();
+        } else {
+            wait_vmcnt0();
+        }
+        block_sync();
 
+        int cur = 0;
         for (int it = 0; it < n_iter; ++it) {
-            const int cur = it & 1;
-            const bool more = it + 1 < n_iter;
+            const int fill = cur == 0 ? 2 : cur - 1;        // (cur + 2) % 3
+            const bool more = it + 2 < n_iter;
             read_step(cur, 0, 0);
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
                 if (j < 3)
                     read_step(cur, j + 1, (j + 1) & 1);
                 mma_step(j & 1);
-                // a quarter of this wave's loads for the next block after each group of MFMAs
                 __builtin_amdgcn_sched_barrier(0);
                 if (more) {
 #pragma unroll
                     for (int q = 0; q < PER_OP / 2; ++q)
-                        issue_one(cur ^ 1, j * (PER_OP / 2) + q);
+                        issue_one(fill, j * (PER_OP / 2) + q);
                 }
                 __builtin_amdgcn_sched_barrier(0);
             }
             if (more)
                 advance();
-            wait_vmcnt0();
-            __syncthreads();
+            if (more && counted)
+                wait_vmcnt_le<L>();             // block it + 1 has landed; it + 2 may fly
+            else
+                wait_vmcnt0();
+            wait_lgkmcnt0();
+            block_sync();
+            cur = cur == 2 ? 0 : cur + 1;
         }
     }
 
-    // ---- epilogue: beta*C, bias, ReLU, store (or raw partial tile for a split)
-    const int64_t m_base = m0 + wm * 64 + (lane & 31);
-    const int64_t n_base = n0 + wn * WN + 4 * (lane >> 5);
-    if (p.split > 1) {
-        float *part = p.partial + (int64_t)blockIdx.y * p.M * p.N;
-        const bool vec = (p.N & 3) == 0;
-        static_for<0, 2>([&](auto bc) {
-            constexpr int b = decltype(bc)::value;
-            const int64_t m = m_base + b * 32;
-            if (m < p.M) {
-                static_for<0, 4 * TN>([&](auto aq) {
-                    constexpr int a = decltype(aq)::value / 4, q = decltype(aq)::value % 4;
-                    const int64_t n = n_base + a * 32 + q * 8;
-                    store4_partial(part + m * p.N + n, p.N - n, vec, acc[a][b][4 * q + 0], acc[a][b][4 * q + 1],
-                                   acc[a][b][4 * q + 2], acc[a][b][4 * q + 3]);
-                });
-            }
+    // ---- epilogue: beta*C, bias, ReLU, store (or raw partial tile for a split).
+    // A lane holds 4 consecutive columns of 32 different rows, which would make every
+    // global access touch 32 cache lines for 32 bytes each.  Each 32x32 accumulator
+    // block therefore goes through this wave's own 4.5 KiB of LDS (all stages are free
+    // after the last barrier; 144-byte row pitch: conflict-free 128-bit writes) and is
+    // read back row-wise, so that one instruction covers 8 rows x 128 bytes: whole
+    // cache lines for the store and for the read of the old C when beta != 0.
+    constexpr int EPI_LD = 36;
+    LDS_AS float *stage = (LDS_AS float *)(smem + (uint32_t)w * (32 * EPI_LD * 4));
+    const bool to_partial = p.split > 1;
+    float *part = to_partial ? p.partial + (int64_t)blockIdx.y * p.M * p.N : nullptr;
+    const bool vec = to_partial ? ((p.N & 3) == 0) : ((p.epi.ldc & 3) == 0 && (((uintptr_t)p.epi.C) & 15) == 0);
+    static_for<0, 2 * TN>([&](auto bc) {
+        constexpr int b = decltype(bc)::value / TN, a = decltype(bc)::value % TN;
+        asm volatile("" ::: "memory");
+        static_for<0, 4>([&](auto qc) {
+            constexpr int q = decltype(qc)::value;
+            *(LDS_AS f32x4 *)(stage + (lane & 31) * EPI_LD + 8 * q + 4 * (lane >> 5)) =
+                f32x4{acc[a][b][4 * q + 0], acc[a][b][4 * q + 1], acc[a][b][4 * q + 2], acc[a][b][4 * q + 3]};
         });
-    } else {
-        const bool vec = (p.epi.ldc & 3) == 0 && (((uintptr_t)p.epi.C) & 15) == 0;
-        static_for<0, 2>([&](auto bc) {
-            constexpr int b = decltype(bc)::value;
-            const int64_t m = m_base + b * 32;
+        asm volatile("" ::: "memory");
+        __builtin_amdgcn_wave_barrier();
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int idx = i * 64 + lane;
+            const int row = idx >> 3, c4 = idx & 7;
+            const f32x4 v = *(LDS_AS f32x4 *)(stage + row * EPI_LD + c4 * 4);
+            const int64_t m = m0 + wm * 64 + b * 32 + row;
+            const int64_t n = n0 + wn * WN + a * 32 + c4 * 4;
             if (m < p.M) {
-                static_for<0, 4 * TN>([&](auto aq) {
-                    constexpr int a = decltype(aq)::value / 4, q = decltype(aq)::value % 4;
-                    const int64_t n = n_base + a * 32 + q * 8;
-                    store4_epilogue(p.epi, m, n, p.N - n, vec, acc[a][b][4 * q + 0], acc[a][b][4 * q + 1],
-                                    acc[a][b][4 * q + 2], acc[a][b][4 * q + 3]);
-                });
+                if (to_partial)
+                    store4_partial(part + m * p.N + n, p.N - n, vec, v[0], v[1], v[2], v[3]);
+                else
+                    store4_epilogue(p.epi, m, n, p.N - n, vec, v[0], v[1], v[2], v[3]);
             }
-        });
-    }
+        }
+        __builtin_amdgcn_wave_barrier();
+    });
 }
 
 hipError_t launch_f32_128x128(const Problem &p)
@@ -261,7 +292,7 @@ hipError_t launch_f32_128x128(const Problem &p)
     a.tiles_m = (int)((p.M + FB - 1) / FB);
     a.tiles_n = (int)((p.N + FB - 1) / FB);
     const dim3 grid((unsigned)(a.tiles_m * a.tiles_n), (unsigned)p.split);
-    const size_t lds = 2 * (size_t)F_STAGE;
+    const size_t lds = 3 * (size_t)F_STAGE;
     const bool ak = p.transA == 0, bk = p.transB == 1;
     void (*kern)(F32Args) = nullptr;
     constexpr int NW = 8;

@@ -381,3 +381,24 @@ def test_stream_variants_ragged_edges_and_splits(oracle, M, N, K, tB):
             out, _ = H.run_gemm_case(case, ldc=N + pad, workspace_bytes=ws, force=(names.index(name), split))
             assert np.isfinite(H.widen(out)).all(), "padding (NaN) leaked into the result"
             assert H.rel_fro(H.widen(out), ref) <= H.TOL_BF16_F32OUT, (name, split)
+
+
+@pytest.mark.gpu
+@pytest.mark.parametrize("tA,tB", [(0, 0), (0, 1), (1, 0), (1, 1)])
+def test_pingpong_and_f32_edge_tiles_with_skipped_wave_loads(oracle, tA, tB):
+    """Tiles that overhang the matrix so far that whole 8-row wave-loads have no live
+    lane: the kernels that count outstanding loads must not count those."""
+    M, N, K = 256 + 104, 512 + 8, 1024
+    names = B.variants()
+    for dtype, vname in (("bf16", "bf16_pingpong_256x256x64"), ("f32", "f32_128x128x32")):
+        Al = W.normal_f32(72, 0, (M, K))
+        Bl = W.normal_f32(72, 1, (K, N))
+        As = np.ascontiguousarray(Al.T if tA else Al)
+        Bs = np.ascontiguousarray(Bl.T if tB else Bl)
+        if dtype == "bf16":
+            As, Bs = W.to_bf16_bits(As), W.to_bf16_bits(Bs)
+        case = W.GemmCase(f"edge_{dtype}_t{tA}{tB}", dtype, M, N, K, tA, tB, 0.0, As, Bs, None, True)
+        say(case.name)
+        ref = H.oracle_gemm_case(oracle, case)
+        out, _ = H.run_gemm_case(case, force=(names.index(vname), 1))
+        assert H.rel_fro(H.widen(out), ref) <= 1e-5, vname
