@@ -166,7 +166,7 @@ def main():
     if not args.no_others:
         others = {}
 
-        def record(name, flops_, fn, peak, steps=50, warmup=5, bytes_=None):
+        def record(name, flops_, fn, peak, steps=50, warmup=20, bytes_=None):
             w_, e_ = time_launches(fn, steps, warmup)
             med_, min_ = per_launch(fn, 20, group=1 if e_ > 50e-6 else 20)
             r = {"us": round(e_ * 1e6, 2), "us_median": round(med_ * 1e6, 2), "us_min": round(min_ * 1e6, 2),

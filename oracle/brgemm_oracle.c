@@ -208,3 +208,33 @@ int oracle_brgemm(int in_dtype, int transA, int transB,
     }
     return bad ? -1 : 0;
 }
+
+/*
+ * VNNI packing of the B operand (Section 2.2 and Figure 1): the K dimension is cut
+ * into groups of v consecutive rows and the v elements of one column within a
+ * group are stored next to each other,
+ *
+ *     out[(k / v) * n_pitch * v + n * v + (k % v)] = B[k][n],
+ *
+ * which turns a K x N matrix into a (K / v) x N x v one (Figure 1: a flat 4 x 4
+ * matrix becomes 2 x 4 x 2 for v = 2).  B is read through transB / ldb like the
+ * GEMM operand (transB == 1: stored N x K).  The output has k_rows rows of k
+ * (k_rows >= K, a multiple of v) and n_pitch >= N columns per group; everything
+ * that does not come from B (rows K.., columns N..) is zero.  Elements are 16-bit
+ * patterns and are moved, never converted.
+ * Returns 0, or -1 on a bad argument.
+ */
+int oracle_pack_vnni(int v, int transB, int64_t K, int64_t N, const uint16_t *B, int64_t ldb,
+                     int64_t k_rows, int64_t n_pitch, uint16_t *out)
+{
+    if (v <= 0 || K < 0 || N < 0 || k_rows < K || k_rows % v != 0 || n_pitch < N)
+        return -1;
+    for (int64_t i = 0; i < k_rows * n_pitch; ++i)
+        out[i] = 0;
+    for (int64_t k = 0; k < K; ++k)
+        for (int64_t n = 0; n < N; ++n) {
+            const uint16_t e = transB ? B[n * ldb + k] : B[k * ldb + n];
+            out[(k / v) * n_pitch * v + n * v + (k % v)] = e;
+        }
+    return 0;
+}

@@ -46,6 +46,8 @@ def _load():
     lib.oracle_bf16_to_f64.argtypes = [ctypes.c_uint16]
     lib.oracle_num_threads.restype = cint
     lib.oracle_num_threads.argtypes = []
+    lib.oracle_pack_vnni.restype = cint
+    lib.oracle_pack_vnni.argtypes = [cint, cint, i64, i64, vp, i64, i64, i64, vp]
     _lib = lib
     return lib
 
@@ -151,3 +153,16 @@ def bf16_to_f64(bits):
         return float(_load().oracle_bf16_to_f64(int(bits)))
     b = np.asarray(bits, dtype=np.uint16)
     return (b.astype(np.uint32) << 16).view(np.float32).astype(np.float64)
+
+
+def pack_vnni(B, ldb, K, N, v, *, transB=0, k_rows=None, n_pitch=None):
+    """VNNI packing (Section 2.2, Figure 1) of a K x N matrix of 16-bit patterns:
+    returns an array of shape (k_rows / v, n_pitch, v), zero outside B."""
+    B = np.ascontiguousarray(B, dtype=np.uint16)
+    k_rows = K + (-K) % v if k_rows is None else k_rows
+    n_pitch = N if n_pitch is None else n_pitch
+    out = np.empty((k_rows // v, n_pitch, v), dtype=np.uint16)
+    rc = _load().oracle_pack_vnni(v, int(transB), K, N, _ptr(B), ldb, k_rows, n_pitch, _ptr(out))
+    if rc != 0:
+        raise ValueError("oracle_pack_vnni rejected its arguments")
+    return out

@@ -396,3 +396,70 @@ def test_empty_shapes(oracle):
     assert np.array_equal(oracle.gemm_ref(A, 1, B, 5, 4, 5, 0, beta=3.0, C0=C0), 3.0 * np.ones((4, 5)))
     assert np.array_equal(oracle.gemm_ref(A, 1, B, 5, 4, 5, 0), np.zeros((4, 5)))
     assert oracle.gemm_ref(A, 1, B, 5, 0, 5, 0).shape == (0, 5)
+
+
+# ---------------------------------------------------------------- VNNI packer (Section 2.2, Figure 1)
+
+def _read_fig1():
+    import os
+    path = os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden", "fig1_vnni2_pack.txt")
+    lines = [l.strip() for l in open(path) if l.strip() and not l.startswith("#")]
+    assert lines[0].split()[0] == "flat"
+    r, c = map(int, lines[0].split()[1:])
+    flat = np.array([[int(x) for x in lines[1 + i].split()] for i in range(r)], dtype=np.uint16)
+    assert flat.shape == (r, c)
+    g, cc, v = map(int, lines[1 + r].split()[1:])
+    packed = np.array([[[int(x) for x in pair.split(",")] for pair in lines[2 + r + i].split()] for i in range(g)],
+                      dtype=np.uint16)
+    assert packed.shape == (g, cc, v)
+    return flat, packed
+
+
+def test_pack_vnni_reproduces_figure_1(oracle):
+    """The paper's worked example: a flat 4x4 matrix and its VNNI:2 packed form."""
+    flat, packed = _read_fig1()
+    got = oracle.pack_vnni(flat, 4, 4, 4, 2)
+    assert got.shape == (2, 4, 2)
+    assert (got == packed).all()
+    # the same matrix handed over transposed (stored N x K) packs to the same image
+    assert (oracle.pack_vnni(np.ascontiguousarray(flat.T), 4, 4, 4, 2, transB=1) == packed).all()
+
+
+@pytest.mark.parametrize("v", [2, 4, 8])
+@pytest.mark.parametrize("K,N", [(8, 5), (13, 7), (64, 33), (1, 1)])
+def test_pack_vnni_against_reshape_and_inverse(oracle, v, K, N):
+    """Where K is a multiple of v the packing is the textbook reshape/transposition
+    (K/v, v, N) -> (K/v, N, v); in general unpacking gives B back and the rest is zero."""
+    rng = np.random.default_rng(7 * v + K + N)
+    Bm = rng.integers(1, 65535, size=(K, N + 3)).astype(np.uint16)      # padded leading dimension
+    got = oracle.pack_vnni(Bm, N + 3, K, N, v)
+    Kp = K + (-K) % v
+    assert got.shape == (Kp // v, N, v)
+    full = np.zeros((Kp, N), dtype=np.uint16)
+    full[:K] = Bm[:, :N]
+    assert (got == full.reshape(Kp // v, v, N).transpose(0, 2, 1)).all()
+    # inverse: element (k, n) sits at [k // v, n, k % v]
+    for k in range(K):
+        for n in range(N):
+            assert got[k // v, n, k % v] == Bm[k, n]
+    # padded image: more k rows and a wider column pitch, all extra entries zero
+    big = oracle.pack_vnni(Bm, N + 3, K, N, v, k_rows=Kp + 2 * v, n_pitch=N + 5)
+    assert (big[:Kp // v, :N] == got).all()
+    assert big[Kp // v:].sum() == 0 and big[:, N:].sum() == 0
+    # transposed storage gives the same image
+    BT = np.ascontiguousarray(Bm[:, :N].T)
+    assert (oracle.pack_vnni(BT, K, K, N, v, transB=1) == got).all()
+
+
+def test_packed_gemm_identity(oracle):
+    """Contracting A against the unpacked image equals the plain product: the packed
+    layout is a pure re-indexing (sum over g, j of A[m, 8g + j] * P[g, n, j])."""
+    M, N, K, v = 5, 6, 24, 8
+    A = W.small_int_matrix(50, (M, K))
+    Bm = W.small_int_matrix(51, (K, N))
+    P = oracle.pack_vnni(bf16_bits(Bm), N, K, N, v)
+    Pv = oracle.bf16_to_f64(P)
+    want = np.einsum("mgj,gnj->mn", A.astype(np.float64).reshape(M, K // v, v), Pv)
+    ref = oracle.gemm_ref(bf16_bits(A), K, bf16_bits(Bm), N, M, N, K)
+    assert (ref == want).all()
+    assert (ref == (A.astype(np.int64) @ Bm.astype(np.int64))).all()
