@@ -216,6 +216,33 @@ def main():
                     record(f"mlp_{which}_M{Mm}_cold", 2.0 * Mm * Nn * Kk, cold, PEAK_BF16, steps=100, bytes_=bytes_)
                 del a, c
             del wgts, wgt
+        # the same GEMMs with B packed once beforehand (Section 2.2; packing is not timed)
+        def packed_of(b, tB, Kk, Nn):
+            pk = torch.empty(B.gemm_packed_b_bytes(Kk, Nn) // 2, dtype=torch.int16, device="cuda")
+            B.gemm_pack_b_bf16(tB, Kk, Nn, b, b.shape[1], pk)
+            return pk
+        a = torch.randn((4096, 4096), device="cuda").to(torch.bfloat16)
+        b = torch.randn((4096, 4096), device="cuda").to(torch.bfloat16)
+        c = torch.empty((4096, 4096), device="cuda", dtype=torch.bfloat16)
+        pk = packed_of(b, 0, 4096, 4096)
+        record("bf16_4096_packedB", 2.0 * 4096 ** 3,
+               lambda: B.gemm_bf16_packed(0, 4096, 4096, 4096, a, 4096, pk, 0.0, c, 4096, 0, workspace=ws), PEAK_BF16,
+               steps=100)
+        del a, b, c, pk
+        for Mm in (4096, 16):
+            Kk, Nn = 4096, 11008
+            pks = [packed_of((torch.randn((Nn, Kk), device="cuda") * 0.02).to(torch.bfloat16), 1, Kk, Nn)
+                   for _ in range(4 if Mm == 16 else 1)]
+            a = torch.randn((Mm, Kk), device="cuda").to(torch.bfloat16)
+            c = torch.empty((Mm, Nn), device="cuda", dtype=torch.bfloat16)
+            turn = [0]
+
+            def packed_step():
+                turn[0] = (turn[0] + 1) % len(pks)
+                B.gemm_bf16_packed(0, Mm, Nn, Kk, a, Kk, pks[turn[0]], 0.0, c, Nn, 0, workspace=ws)
+            record(f"mlp_up_M{Mm}_packedB" + ("_cold" if Mm == 16 else ""), 2.0 * Mm * Nn * Kk, packed_step, PEAK_BF16,
+                   steps=30 if Mm == 4096 else 100, bytes_=2.0 * (Mm * Kk + Kk * Nn + Mm * Nn) if Mm == 16 else None)
+            del a, c, pks
         # batch-reduce over scattered tiles
         c5 = W.config5_brgemm()
         pool = dev(c5.pool)

@@ -125,6 +125,43 @@ int brgemm_fused(int in_dtype, int transA, int transB,
                  void *workspace, size_t workspace_bytes, void *stream);
 
 /*
+ * Pre-packed B ("VNNI-packed layout", Section 2.2 and Figure 1; the comparison of
+ * packed against flat operands is the axis of the paper's evaluation, Section 6).
+ * Weights that are used many times can be re-laid-out once so that the kernels
+ * fetch them with straight 16-byte copies and feed the matrix instruction with
+ * plain LDS reads - no transposing reads, no swizzle.
+ *
+ * gemm_pack_vnni_bf16: the packing of Figure 1 for any factor vnni in {2, 4, 8}:
+ *     out[(k / vnni) * n_pitch * vnni + n * vnni + k % vnni] = B[k][n]
+ * for a logical K x N matrix B of 16-bit elements read through transB / ldb as in
+ * gemm_bf16.  out (device, 16-byte aligned) holds k_rows / vnni groups of n_pitch
+ * columns of vnni elements; k_rows >= K must be a multiple of vnni, n_pitch >= N;
+ * entries outside B are written as zero.  Figure 1 is vnni = 2 on a 4 x 4 matrix.
+ *
+ * gemm_packed_b_bytes / gemm_pack_b_bf16: the image the GEMM below reads: vnni = 8
+ * (the 8 bf16 values one lane of the matrix instruction consumes), k_rows = K
+ * rounded up to a multiple of 64, n_pitch = N rounded up to a multiple of 256.
+ * packed: device, 16-byte aligned, at least gemm_packed_b_bytes(K, N) bytes
+ * (packed_bytes says how many there are; too few is BRGEMM_INVALID_ARG).
+ *
+ * gemm_bf16_packed: C = act(beta*C + A x B + bias) with B given as that image
+ * (packedB: device, 16-byte aligned, written by gemm_pack_b_bf16 for the same K and
+ * N and complete before this call runs on the stream).  All other arguments as in
+ * gemm_bf16 / brgemm_fused; results are identical to gemm_bf16 on the unpacked B up
+ * to the order of the fp32 summation.
+ */
+int gemm_pack_vnni_bf16(int vnni, int transB, int64_t K, int64_t N, const uint16_t *B, int64_t ldb,
+                        int64_t k_rows, int64_t n_pitch, uint16_t *out, void *stream);
+size_t gemm_packed_b_bytes(int64_t K, int64_t N);
+int gemm_pack_b_bf16(int transB, int64_t K, int64_t N, const uint16_t *B, int64_t ldb,
+                     uint16_t *packed, size_t packed_bytes, void *stream);
+int gemm_bf16_packed(int transA, int64_t M, int64_t N, int64_t K,
+                     const uint16_t *A, int64_t lda, const uint16_t *packedB,
+                     float beta, void *C, int64_t ldc, int c_is_f32,
+                     const float *bias, int epilogue,
+                     void *workspace, size_t workspace_bytes, void *stream);
+
+/*
  * Upper bound, in bytes, of the workspace any variant may use for a problem of
  * this element type and size (batch = 1 for the GEMM calls).  Never fails;
  * returns 0 for empty problems.

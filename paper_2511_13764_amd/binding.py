@@ -28,7 +28,8 @@ EPI_NONE, EPI_BIAS, EPI_RELU = 0, 1, 2
 
 EXPORTS = ["gemm_f32", "gemm_bf16", "brgemm_bf16", "brgemm_fused", "gemm_workspace_bytes",
            "gemm_strerror", "gemm_last_hip_error", "gemm_force_variant", "gemm_variant_name",
-           "gemm_last_variant", "gemm_last_split", "gemm_mfma_probe"]
+           "gemm_last_variant", "gemm_last_split", "gemm_mfma_probe", "gemm_pack_vnni_bf16",
+           "gemm_packed_b_bytes", "gemm_pack_b_bf16", "gemm_bf16_packed"]
 
 _lib = None
 
@@ -73,6 +74,14 @@ def load():
     lib.gemm_last_variant.argtypes = []
     lib.gemm_last_split.restype = ci
     lib.gemm_last_split.argtypes = []
+    lib.gemm_pack_vnni_bf16.restype = ci
+    lib.gemm_pack_vnni_bf16.argtypes = [ci, ci, i64, i64, vp, i64, i64, i64, vp, vp]
+    lib.gemm_packed_b_bytes.restype = sz
+    lib.gemm_packed_b_bytes.argtypes = [i64, i64]
+    lib.gemm_pack_b_bf16.restype = ci
+    lib.gemm_pack_b_bf16.argtypes = [ci, i64, i64, vp, i64, vp, sz, vp]
+    lib.gemm_bf16_packed.restype = ci
+    lib.gemm_bf16_packed.argtypes = [ci, i64, i64, i64, vp, i64, vp, cf, vp, i64, ci, vp, ci, vp, sz, vp]
     lib.gemm_mfma_probe.restype = ci
     lib.gemm_mfma_probe.argtypes = [ci, vp, i64, ci, vp, ctypes.POINTER(ctypes.c_double), vp]
     _lib = lib
@@ -138,6 +147,30 @@ def brgemm_fused(in_dtype, transA, transB, M, N, K, batch, A_base, A_off, lda, B
                              _ptr(B_base), _ptr(B_off), ldb, beta, _ptr(C), ldc, int(bool(c_is_f32)),
                              _ptr(bias), epilogue, ws, nb, _stream(stream))
     return _check(rc, "brgemm_fused", check)
+
+
+def gemm_pack_vnni_bf16(vnni, transB, K, N, B, ldb, k_rows, n_pitch, out, stream=None, check=True):
+    rc = load().gemm_pack_vnni_bf16(vnni, transB, K, N, _ptr(B), ldb, k_rows, n_pitch, _ptr(out), _stream(stream))
+    return _check(rc, "gemm_pack_vnni_bf16", check)
+
+
+def gemm_packed_b_bytes(K, N):
+    return int(load().gemm_packed_b_bytes(K, N))
+
+
+def gemm_pack_b_bf16(transB, K, N, B, ldb, packed, packed_bytes=None, stream=None, check=True):
+    if packed_bytes is None:
+        packed_bytes = packed.numel() * packed.element_size()
+    rc = load().gemm_pack_b_bf16(transB, K, N, _ptr(B), ldb, _ptr(packed), packed_bytes, _stream(stream))
+    return _check(rc, "gemm_pack_b_bf16", check)
+
+
+def gemm_bf16_packed(transA, M, N, K, A, lda, packedB, beta, C, ldc, c_is_f32, bias=None, epilogue=0,
+                     workspace=None, stream=None, check=True):
+    ws, nb = _ws(workspace)
+    rc = load().gemm_bf16_packed(transA, M, N, K, _ptr(A), lda, _ptr(packedB), beta, _ptr(C), ldc,
+                                 int(bool(c_is_f32)), _ptr(bias), epilogue, ws, nb, _stream(stream))
+    return _check(rc, "gemm_bf16_packed", check)
 
 
 def gemm_mfma_probe(dtype, operands, iters, blocks, sink, stream=None, check=True):

@@ -20,6 +20,8 @@ inline int64_t stored_cols_b(const Problem &p) { return p.transB ? p.K : p.N; }
 
 constexpr int64_t kMaxDim = 2147483647LL;
 
+inline int64_t round_up(int64_t x, int64_t to) { return (x + to - 1) / to * to; }
+
 int validate(const Problem &p, const void *workspace, size_t workspace_bytes, bool need_offsets)
 {
     if ((p.transA | 1) != 1 || (p.transB | 1) != 1)
@@ -161,6 +163,69 @@ int brgemm_fused(int in_dtype, int transA, int transB,
     p.M = M; p.N = N; p.K = K; p.batch = batch;
     p.A = A_base; p.A_off = A_off; p.lda = lda;
     p.B = B_base; p.B_off = B_off; p.ldb = ldb;
+    p.beta = beta; p.C = C; p.ldc = ldc; p.c_f32 = c_is_f32 ? 1 : 0;
+    p.bias = (epilogue & BRGEMM_EPI_BIAS) ? bias : nullptr;
+    p.relu = (epilogue & BRGEMM_EPI_RELU) ? 1 : 0;
+    p.stream = (hipStream_t)stream;
+    return run(p, workspace, workspace_bytes, false);
+}
+
+int gemm_pack_vnni_bf16(int vnni, int transB, int64_t K, int64_t N, const uint16_t *B, int64_t ldb,
+                        int64_t k_rows, int64_t n_pitch, uint16_t *out, void *stream)
+{
+    if ((transB | 1) != 1 || K < 0 || N < 0 || K > kMaxDim || N > kMaxDim)
+        return BRGEMM_INVALID_ARG;
+    if (vnni != 2 && vnni != 4 && vnni != 8)
+        return BRGEMM_INVALID_ARG;
+    if (k_rows < K || k_rows % vnni != 0 || n_pitch < N || k_rows > kMaxDim || n_pitch > kMaxDim)
+        return BRGEMM_INVALID_ARG;
+    if (k_rows == 0 || n_pitch == 0)
+        return BRGEMM_OK;
+    if (!out || ((uintptr_t)out & 15u))
+        return BRGEMM_INVALID_ARG;
+    if (K > 0 && N > 0 && (!B || ldb < (transB ? K : N)))
+        return BRGEMM_INVALID_ARG;
+    return finish(launch_pack_vnni(vnni, transB, K, N, B, ldb, k_rows, n_pitch, out, (hipStream_t)stream));
+}
+
+size_t gemm_packed_b_bytes(int64_t K, int64_t N)
+{
+    if (K <= 0 || N <= 0 || K > kMaxDim || N > kMaxDim)
+        return 0;
+    return (size_t)round_up(K, 64) * (size_t)round_up(N, 256) * sizeof(uint16_t);
+}
+
+int gemm_pack_b_bf16(int transB, int64_t K, int64_t N, const uint16_t *B, int64_t ldb,
+                     uint16_t *packed, size_t packed_bytes, void *stream)
+{
+    if (K < 0 || N < 0 || K > kMaxDim || N > kMaxDim)
+        return BRGEMM_INVALID_ARG;
+    if (K == 0 || N == 0)
+        return BRGEMM_OK;
+    if (packed_bytes < gemm_packed_b_bytes(K, N))
+        return BRGEMM_INVALID_ARG;
+    return gemm_pack_vnni_bf16(8, transB, K, N, B, ldb, round_up(K, 64), round_up(N, 256), packed, stream);
+}
+
+int gemm_bf16_packed(int transA, int64_t M, int64_t N, int64_t K,
+                     const uint16_t *A, int64_t lda, const uint16_t *packedB,
+                     float beta, void *C, int64_t ldc, int c_is_f32,
+                     const float *bias, int epilogue,
+                     void *workspace, size_t workspace_bytes, void *stream)
+{
+    if (epilogue & ~(BRGEMM_EPI_BIAS | BRGEMM_EPI_RELU))
+        return BRGEMM_INVALID_ARG;
+    if ((epilogue & BRGEMM_EPI_BIAS) && !bias && N > 0)
+        return BRGEMM_INVALID_ARG;
+    if (packedB && ((uintptr_t)packedB & 15u))
+        return BRGEMM_INVALID_ARG;
+    if (N > kMaxDim - 256)
+        return BRGEMM_INVALID_ARG;
+    Problem p{};
+    p.in_bf16 = 1; p.transA = transA; p.transB = 0; p.b_packed = 1;
+    p.M = M; p.N = N; p.K = K; p.batch = 1;
+    p.A = A; p.lda = lda;
+    p.B = packedB; p.ldb = N > 0 ? round_up(N, 256) * 8 : 0;
     p.beta = beta; p.C = C; p.ldc = ldc; p.c_f32 = c_is_f32 ? 1 : 0;
     p.bias = (epilogue & BRGEMM_EPI_BIAS) ? bias : nullptr;
     p.relu = (epilogue & BRGEMM_EPI_RELU) ? 1 : 0;

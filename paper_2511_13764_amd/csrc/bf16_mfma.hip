@@ -22,12 +22,12 @@
 
 namespace brg {
 
-template <int BM, int BN, bool A_KMAJ, bool B_KMAJ>
+template <int BM, int BN, bool A_KMAJ, int B_LAY>
 __global__ void __launch_bounds__(256)
 bf16_mfma_kernel(Bf16Args p)
 {
     typedef typename TileOf<BM, 4, A_KMAJ>::type ATile;
-    typedef typename TileOf<BN, 4, B_KMAJ>::type BTile;
+    typedef typename TileOf<BN, 4, B_LAY>::type BTile;
     constexpr int WM = BM / 2, WN = BN / 2;         // wave tile
     constexpr int TM = WM / 32, TN = WN / 32;       // MFMA tiles per wave tile
     constexpr uint32_t A_BYTES = BM * BK * 2, B_BYTES = BN * BK * 2;
@@ -63,10 +63,10 @@ bf16_mfma_kernel(Bf16Args p)
 #pragma unroll
     for (int j = 0; j < BTile::kPerWave; ++j)
         b_src[j] = BTile::src_rel_bytes(w, j, lane, n0, p.N, p.ldb);
-    const int64_t a_origin = A_KMAJ ? m0 * p.lda : m0;
-    const int64_t b_origin = B_KMAJ ? n0 * p.ldb : n0;
-    const int64_t a_kstep = A_KMAJ ? (int64_t)BK : (int64_t)BK * p.lda;
-    const int64_t b_kstep = B_KMAJ ? (int64_t)BK : (int64_t)BK * p.ldb;
+    const int64_t a_origin = ATile::origin(m0, p.lda);
+    const int64_t b_origin = BTile::origin(n0, p.ldb);
+    const int64_t a_kstep = ATile::kstep(p.lda);
+    const int64_t b_kstep = BTile::kstep(p.ldb);
 
     // Load cursor: the (batch index, k-block) of the next block to request, and the
     // operand pointers that go with it.  Advanced without divisions.
@@ -220,13 +220,16 @@ static hipError_t launch_tile(const Problem &p)
     a.tiles_n = (int)((p.N + BN - 1) / BN);
     const dim3 grid((unsigned)(a.tiles_m * a.tiles_n), (unsigned)p.split);
     const size_t lds = 2 * (size_t)(BM + BN) * BK * 2;
-    const bool ak = p.transA == 0, bk = p.transB == 1;
+    const bool ak = p.transA == 0;
+    const int lay = p.b_packed ? LAY_PACKED : (p.transB == 1 ? LAY_K : LAY_MN);
     void (*kern)(Bf16Args) = nullptr;
-    if (ak && bk) kern = bf16_mfma_kernel<BM, BN, true, true>;
-    else if (ak && !bk) kern = bf16_mfma_kernel<BM, BN, true, false>;
-    else if (!ak && bk) kern = bf16_mfma_kernel<BM, BN, false, true>;
-    else kern = bf16_mfma_kernel<BM, BN, false, false>;
-    static thread_local const void *configured[8] = {nullptr};
+    if (ak && lay == LAY_K) kern = bf16_mfma_kernel<BM, BN, true, LAY_K>;
+    else if (ak && lay == LAY_MN) kern = bf16_mfma_kernel<BM, BN, true, LAY_MN>;
+    else if (ak) kern = bf16_mfma_kernel<BM, BN, true, LAY_PACKED>;
+    else if (lay == LAY_K) kern = bf16_mfma_kernel<BM, BN, false, LAY_K>;
+    else if (lay == LAY_MN) kern = bf16_mfma_kernel<BM, BN, false, LAY_MN>;
+    else kern = bf16_mfma_kernel<BM, BN, false, LAY_PACKED>;
+    static thread_local const void *configured[12] = {nullptr};
     bool done = false;
     for (const void *c : configured)
         done = done || c == (const void *)kern;
@@ -255,7 +258,7 @@ bool bf16_mfma_eligible(const Problem &p)
         return false;
     if (p.transA == 1 && (p.M & 7))
         return false;
-    if (p.transB == 0 && (p.N & 7))
+    if (!p.b_packed && p.transB == 0 && (p.N & 7))
         return false;
     if (p.lda >= (1 << 22) || p.ldb >= (1 << 22))
         return false;

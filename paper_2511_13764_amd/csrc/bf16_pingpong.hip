@@ -53,13 +53,13 @@ __device__ __forceinline__ void phase_sync()
 // offsets that are not 16-byte aligned).  EDGE: the tile overhangs the matrix in the
 // direction this wave loads, so lanes outside it are switched off.  Both are uniform
 // over the workgroup / wave and chosen once, so the loop body carries no branches for them.
-template <bool A_KMAJ, bool B_KMAJ, bool DIRECT, bool EDGE>
+template <bool A_KMAJ, int B_LAY, bool DIRECT, bool EDGE>
 __device__ __forceinline__ void pp_body(const Bf16Args &p)
 {
     // Load duty: waves 0-3 fetch the B halves, waves 4-7 the A halves (8 wave-loads
     // per half-block each), so the tile classes are instantiated for 4 loader waves.
     typedef typename TileOf<PP_BM, 4, A_KMAJ>::type ATile;
-    typedef typename TileOf<PP_BN, 4, B_KMAJ>::type BTile;
+    typedef typename TileOf<PP_BN, 4, B_LAY>::type BTile;
     static_assert(ATile::kPerWave == 8 && BTile::kPerWave == 8, "8 wave-loads per loader wave");
 
     extern __shared__ __attribute__((aligned(1024))) char smem_generic[];
@@ -91,12 +91,10 @@ __device__ __forceinline__ void pp_body(const Bf16Args &p)
     const int64_t op_ld = group ? p.lda : p.ldb;
     const int64_t op_first = group ? m0 : n0;             // first row / column of the tile
     const int64_t op_limit = group ? p.M : p.N;
-    const int64_t op_origin = group ? (A_KMAJ ? m0 * p.lda : m0) : (B_KMAJ ? n0 * p.ldb : n0);
-    const int64_t op_kstep = group ? (A_KMAJ ? (int64_t)BK : (int64_t)BK * p.lda)
-                                   : (B_KMAJ ? (int64_t)BK : (int64_t)BK * p.ldb);
+    const int64_t op_origin = group ? ATile::origin(m0, p.lda) : BTile::origin(n0, p.ldb);
+    const int64_t op_kstep = group ? ATile::kstep(p.lda) : BTile::kstep(p.ldb);
     const uint32_t lane_off0 = group ? ATile::lane_off_bytes(0, lane, op_ld) : BTile::lane_off_bytes(0, lane, op_ld);
     const uint32_t lane_off1 = group ? ATile::lane_off_bytes(1, lane, op_ld) : BTile::lane_off_bytes(1, lane, op_ld);
-    const int64_t g_stride = group ? ATile::instr_stride_bytes(op_ld) : BTile::instr_stride_bytes(op_ld);
 
     // Load cursor of this wave's operand: next block's (batch index, k-block), its
     // source pointer and its ring slot.  Half-block 2t is A(t), 2t+1 is B(t); slot = index % 5.
@@ -108,7 +106,8 @@ __device__ __forceinline__ void pp_body(const Bf16Args &p)
     // One of the 8 wave-loads of this wave's next half-block.
     auto issue_one = [&](int j) {
         const int gi = wl * 8 + j;
-        const char *gj = (const char *)ld_ptr + (int64_t)gi * g_stride;
+        const char *gj = (const char *)ld_ptr + (group ? ATile::instr_offset_bytes(gi, op_ld)
+                                                       : BTile::instr_offset_bytes(gi, op_ld));
         const uint32_t off = (j & 1) ? lane_off1 : lane_off0;
         const uint32_t dst = (uint32_t)ld_slot * PP_SLOT + (uint32_t)gi * 1024u;
         const bool on = !EDGE || (group ? ATile::lane_valid(gi, lane, op_first, op_limit)
@@ -304,7 +303,7 @@ __device__ __forceinline__ void pp_body(const Bf16Args &p)
     });
 }
 
-template <bool A_KMAJ, bool B_KMAJ>
+template <bool A_KMAJ, int B_LAY>
 __global__ void __launch_bounds__(512)
 bf16_pingpong_kernel(Bf16Args p)
 {
@@ -337,13 +336,14 @@ bf16_pingpong_kernel(Bf16Args p)
     // Does this wave's operand tile overhang the matrix?  (waves 4-7 load A, 0-3 load B)
     int tm, tn;
     tile_coords(blockIdx.x, p.tiles_m, p.tiles_n, tm, tn);
-    const bool edge = (w >> 2) ? ((int64_t)(tm + 1) * PP_BM > p.M) : ((int64_t)(tn + 1) * PP_BN > p.N);
+    const bool edge = (w >> 2) ? ((int64_t)(tm + 1) * PP_BM > p.M)
+                               : (B_LAY != LAY_PACKED && (int64_t)(tn + 1) * PP_BN > p.N);
     if (direct) {
-        if (!edge) pp_body<A_KMAJ, B_KMAJ, true, false>(p);
-        else pp_body<A_KMAJ, B_KMAJ, true, true>(p);
+        if (!edge) pp_body<A_KMAJ, B_LAY, true, false>(p);
+        else pp_body<A_KMAJ, B_LAY, true, true>(p);
     } else {
-        if (!edge) pp_body<A_KMAJ, B_KMAJ, false, false>(p);
-        else pp_body<A_KMAJ, B_KMAJ, false, true>(p);
+        if (!edge) pp_body<A_KMAJ, B_LAY, false, false>(p);
+        else pp_body<A_KMAJ, B_LAY, false, true>(p);
     }
 }
 
@@ -360,13 +360,16 @@ static hipError_t launch_pp(const Problem &p)
     a.tiles_n = (int)((p.N + PP_BN - 1) / PP_BN);
     const dim3 grid((unsigned)(a.tiles_m * a.tiles_n), (unsigned)p.split);
     const size_t lds = (size_t)PP_SLOTS * PP_SLOT;
-    const bool ak = p.transA == 0, bk = p.transB == 1;
+    const bool ak = p.transA == 0;
+    const int lay = p.b_packed ? LAY_PACKED : (p.transB == 1 ? LAY_K : LAY_MN);
     void (*kern)(Bf16Args) = nullptr;
-    if (ak && bk) kern = bf16_pingpong_kernel<true, true>;
-    else if (ak && !bk) kern = bf16_pingpong_kernel<true, false>;
-    else if (!ak && bk) kern = bf16_pingpong_kernel<false, true>;
-    else kern = bf16_pingpong_kernel<false, false>;
-    static thread_local const void *configured[4] = {nullptr};
+    if (ak && lay == LAY_K) kern = bf16_pingpong_kernel<true, LAY_K>;
+    else if (ak && lay == LAY_MN) kern = bf16_pingpong_kernel<true, LAY_MN>;
+    else if (ak) kern = bf16_pingpong_kernel<true, LAY_PACKED>;
+    else if (lay == LAY_K) kern = bf16_pingpong_kernel<false, LAY_K>;
+    else if (lay == LAY_MN) kern = bf16_pingpong_kernel<false, LAY_MN>;
+    else kern = bf16_pingpong_kernel<false, LAY_PACKED>;
+    static thread_local const void *configured[6] = {nullptr};
     bool done = false;
     for (const void *c : configured)
         done = done || c == (const void *)kern;

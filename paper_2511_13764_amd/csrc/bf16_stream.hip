@@ -23,12 +23,12 @@ namespace {
 constexpr int ST_BN = 128;
 constexpr int ST_STAGES = 3;
 
-template <int BM, bool B_KMAJ>
+template <int BM, int B_LAY>
 __global__ void __launch_bounds__(256)
 bf16_stream_kernel(Bf16Args p)
 {
     typedef KMajorTile<BM, 4> ATile;
-    typedef typename TileOf<ST_BN, 4, B_KMAJ>::type BTile;
+    typedef typename TileOf<ST_BN, 4, B_LAY>::type BTile;
     constexpr int WGM = BM == 128 ? 2 : 1, WGN = 4 / WGM;     // wave grid
     constexpr int WM = BM / WGM, WN = ST_BN / WGN;
     constexpr int TM = WM / 32, TN = WN / 32;
@@ -65,9 +65,9 @@ bf16_stream_kernel(Bf16Args p)
 #pragma unroll
     for (int j = 0; j < BTile::kPerWave; ++j)
         b_src[j] = BTile::src_rel_bytes(w, j, lane, n0, p.N, p.ldb);
-    const int64_t b_kstep = B_KMAJ ? (int64_t)BK : (int64_t)BK * p.ldb;
+    const int64_t b_kstep = BTile::kstep(p.ldb);
     const uint16_t *ld_a = uniform_ptr(p.A + m0 * p.lda + (int64_t)it_begin * BK);
-    const uint16_t *ld_b = uniform_ptr(p.B + (B_KMAJ ? n0 * p.ldb : n0) + (int64_t)it_begin * b_kstep);
+    const uint16_t *ld_b = uniform_ptr(p.B + BTile::origin(n0, p.ldb) + (int64_t)it_begin * b_kstep);
     int ld_slot = 0;
 
     auto issue_loads = [&]() {
@@ -148,8 +148,9 @@ hipError_t launch_stream(const Problem &p)
     a.tiles_n = (int)((p.N + ST_BN - 1) / ST_BN);
     const dim3 grid((unsigned)(a.tiles_m * a.tiles_n), (unsigned)p.split);
     const size_t lds = (size_t)ST_STAGES * (BM + ST_BN) * BK * 2;
-    void (*kern)(Bf16Args) = p.transB == 1 ? bf16_stream_kernel<BM, true> : bf16_stream_kernel<BM, false>;
-    static thread_local const void *configured[2] = {nullptr};
+    void (*kern)(Bf16Args) = p.b_packed ? bf16_stream_kernel<BM, LAY_PACKED>
+                             : p.transB == 1 ? bf16_stream_kernel<BM, LAY_K> : bf16_stream_kernel<BM, LAY_MN>;
+    static thread_local const void *configured[3] = {nullptr};
     bool done = false;
     for (const void *c : configured)
         done = done || c == (const void *)kern;

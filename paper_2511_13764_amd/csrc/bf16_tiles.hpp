@@ -135,6 +135,10 @@ struct KMajorTile {
     // lane offset that depends on g only through its parity (the swizzle term 4*(g&1)).
     // Lanes whose row lies outside the matrix are switched off instead of redirected.
     __device__ static int64_t instr_stride_bytes(int64_t ld) { return 8 * ld * 2; }
+    __device__ static int64_t instr_offset_bytes(int g, int64_t ld) { return (int64_t)g * 8 * ld * 2; }
+    // Element offset of the tile's first row, and of one k-block step, in the matrix.
+    __device__ static int64_t origin(int64_t first, int64_t ld) { return first * ld; }
+    __device__ static int64_t kstep(int64_t) { return BK; }
     __device__ static uint32_t lane_off_bytes(int parity, int lane, int64_t ld)
     {
         const int c = (lane & 7) ^ ((4 * parity + (lane >> 4)) & 7);
@@ -196,7 +200,9 @@ struct MNMajorTile {
     // Scalar-base form: wave-instruction g reads k-rows (64/kChunksPerRow)*g.. ; the
     // swizzle term depends on g only through its parity when a row is 32 chunks wide.
     static_assert(kChunksPerRow == 32 || kChunksPerRow == 16, "row of 256 or 128 elements");
-    __device__ static int64_t instr_stride_bytes(int64_t ld) { return (64 / kChunksPerRow) * ld * 2; }
+    __device__ static int64_t instr_offset_bytes(int g, int64_t ld) { return (int64_t)g * (64 / kChunksPerRow) * ld * 2; }
+    __device__ static int64_t origin(int64_t first, int64_t) { return first; }
+    __device__ static int64_t kstep(int64_t ld) { return (int64_t)BK * ld; }
     __device__ static uint32_t lane_off_bytes(int parity, int lane, int64_t ld)
     {
         // rows per instruction: 2 (32 chunks/row) or 4 (16 chunks/row)
@@ -237,12 +243,55 @@ struct MNMajorTile {
     }
 };
 
-template <int EXTENT, int NW, bool KMAJ>
+// ---------------------------------------------------------------------------
+// B operand packed ahead of time in groups of 8 consecutive k: the VNNI layout of
+// Section 2.2 / Figure 1 with a factor of 8, the 8 bf16 values one MFMA lane
+// consumes.  Element (k, n) sits at ((k / 8) * n_pitch + n) * 8 + k % 8; "ld" is
+// the element count of one k-group row, n_pitch * 8.  The packer pads K to a
+// multiple of 64 and the column pitch to a multiple of 256 with zeros, so tiles
+// never overhang the image.  A k-block of a COLS-wide tile is 8 runs of COLS * 16
+// contiguous bytes; the LDS image keeps that order ([k-group][column][16 bytes]),
+// global -> LDS is a straight copy, and a fragment read takes 32 consecutive
+// 16-byte chunks per half-wave: no swizzle, no bank conflicts, no transposing read.
+// ---------------------------------------------------------------------------
+template <int COLS, int NW>
+struct PackedTile {
+    static constexpr int kPerGroup = COLS / 64;             // wave-loads per k-group row
+    static constexpr int kInstr = 8 * kPerGroup;
+    static constexpr int kPerWave = kInstr / NW;
+
+    __device__ static uint32_t dst_byte(int w, int j) { return (uint32_t)(w * kPerWave + j) * 1024u; }
+    __device__ static uint32_t src_rel_bytes(int w, int j, int lane, int64_t, int64_t, int64_t ld)
+    {
+        const int g = w * kPerWave + j;
+        return (uint32_t)(((int64_t)(g / kPerGroup) * ld + (int64_t)(64 * (g % kPerGroup) + lane) * 8) * 2);
+    }
+    __device__ static int64_t instr_offset_bytes(int g, int64_t ld)
+    {
+        return ((int64_t)(g / kPerGroup) * ld + (int64_t)(g % kPerGroup) * 512) * 2;
+    }
+    __device__ static int64_t origin(int64_t first, int64_t) { return first * 8; }
+    __device__ static int64_t kstep(int64_t ld) { return 8 * ld; }
+    __device__ static uint32_t lane_off_bytes(int, int lane, int64_t) { return (uint32_t)lane * 16u; }
+    __device__ static bool lane_valid(int, int, int64_t, int64_t) { return true; }
+    __device__ static bf16x8 read_frag(LDS_AS char *tile, int col_base, int t, int ks, int lane)
+    {
+        const int kg = 2 * ks + (lane >> 5);
+        const int col = col_base + t * 32 + (lane & 31);
+        return *(LDS_AS bf16x8 *)(tile + (uint32_t)(kg * COLS + col) * 16u);
+    }
+};
+
+// Operand layouts as template arguments (a bool "k-major" converts to the first two).
+constexpr int LAY_MN = 0, LAY_K = 1, LAY_PACKED = 2;
+template <int EXTENT, int NW, int LAYOUT>
 struct TileOf;
 template <int EXTENT, int NW>
-struct TileOf<EXTENT, NW, true> { typedef KMajorTile<EXTENT, NW> type; };
+struct TileOf<EXTENT, NW, LAY_K> { typedef KMajorTile<EXTENT, NW> type; };
 template <int EXTENT, int NW>
-struct TileOf<EXTENT, NW, false> { typedef MNMajorTile<EXTENT, NW> type; };
+struct TileOf<EXTENT, NW, LAY_MN> { typedef MNMajorTile<EXTENT, NW> type; };
+template <int EXTENT, int NW>
+struct TileOf<EXTENT, NW, LAY_PACKED> { typedef PackedTile<EXTENT, NW> type; };
 
 // XCD-aware tile order.  Workgroups are dealt round-robin to the 8 XCDs (each with
 // its own L2), so workgroup w is renumbered to t = (w % 8) * (T/8) + w / 8: every

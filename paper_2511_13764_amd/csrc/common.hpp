@@ -19,6 +19,10 @@ struct Problem {
     const void *B;
     const int64_t *B_off;
     int64_t ldb;
+    // 1: B is the image written by the packer (groups of 8 k, Section 2.2 / Figure 1):
+    // element (k, n) at ((k / 8) * n_pitch + n) * 8 + k % 8 with ldb = n_pitch * 8,
+    // n_pitch a multiple of 256, k padded to a multiple of 64 with zeros; transB is 0.
+    int b_packed;
     float beta;
     void *C;
     int64_t ldc;
@@ -103,5 +107,9 @@ hipError_t launch_generic(const Problem &p);
 hipError_t launch_reduce(const Problem &p);
 // beta-only pass for K == 0 or batch == 0: C = act(beta*C + bias).
 hipError_t launch_scale_only(const Problem &p);
+// VNNI-v packing of a K x N matrix of 16-bit elements into k_rows / v groups of
+// n_pitch columns (zero outside the matrix).
+hipError_t launch_pack_vnni(int v, int transB, int64_t K, int64_t N, const uint16_t *B, int64_t ldb,
+                            int64_t k_rows, int64_t n_pitch, uint16_t *out, hipStream_t stream);
 
 }  // namespace brg

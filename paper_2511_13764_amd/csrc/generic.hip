@@ -73,11 +73,12 @@ generic_kernel(int transA, int transB, int64_t M, int64_t N, int64_t K, int64_t 
         }
         for (int e = tid; e < GT * GK; e += 256) {
             int n, k;
-            if (transB) { k = e % GK; n = e / GK; } else { n = e % GT; k = e / GT; }
+            if (transB) { k = e % GK; n = e / GK; } else { n = e % GT; k = e / GT; }      // 2 (packed): k fastest
             const int64_t gn = n0 + n, gk = k0 + k;
             float v = 0.0f;
             if (gn < N && gk < K)
-                v = load_in<BF16>(B, bo + (transB ? gn * ldb + gk : gk * ldb + gn));
+                v = load_in<BF16>(B, bo + (transB == 2 ? (gk >> 3) * ldb + gn * 8 + (gk & 7)
+                                                       : transB ? gn * ldb + gk : gk * ldb + gn));
             Bs[k][n] = v;
         }
         __syncthreads();
@@ -164,7 +165,7 @@ hipError_t launch_generic(const Problem &p)
     dim3 grid((unsigned)((p.N + GT - 1) / GT), (unsigned)((p.M + GT - 1) / GT), (unsigned)p.split);
     Epilogue e = make_epilogue(p);
     if (p.in_bf16)
-        hipLaunchKernelGGL(generic_kernel<true>, grid, dim3(256), 0, p.stream, p.transA, p.transB, p.M, p.N,
+        hipLaunchKernelGGL(generic_kernel<true>, grid, dim3(256), 0, p.stream, p.transA, p.b_packed ? 2 : p.transB, p.M, p.N,
                            p.K, p.batch, p.A, p.A_off, p.lda, p.B, p.B_off, p.ldb, e, p.split, p.partial);
     else
         hipLaunchKernelGGL(generic_kernel<false>, grid, dim3(256), 0, p.stream, p.transA, p.transB, p.M, p.N,

@@ -125,3 +125,29 @@ def test_mfma_probe_rejects_bad_arguments(lib):
         assert rc == 0.0        # rejected before launch: no operation count is reported
         assert lib.gemm_mfma_probe(a["dtype"], a["operands"], a["iters"], a["blocks"], a["sink"], None, 0) == \
             B.INVALID_ARG
+
+
+def test_packed_b_size_and_argument_rules(lib):
+    assert B.gemm_packed_b_bytes(0, 5) == 0 and B.gemm_packed_b_bytes(5, -1) == 0
+    assert B.gemm_packed_b_bytes(1, 1) == 64 * 256 * 2
+    assert B.gemm_packed_b_bytes(4096, 11008) == 4096 * 11008 * 2
+    assert B.gemm_packed_b_bytes(65, 257) == 128 * 512 * 2
+    ok = dict(vnni=8, transB=0, K=16, N=8, B=P, ldb=8, k_rows=16, n_pitch=8, out=P)
+    for kw in (dict(vnni=3), dict(vnni=16), dict(transB=2), dict(K=-1), dict(N=-1), dict(ldb=7), dict(k_rows=8),
+               dict(k_rows=20), dict(n_pitch=7), dict(out=0), dict(out=P + 2), dict(B=0)):
+        a = dict(ok)
+        a.update(kw)
+        rc = B.gemm_pack_vnni_bf16(a["vnni"], a["transB"], a["K"], a["N"], a["B"], a["ldb"], a["k_rows"],
+                                   a["n_pitch"], a["out"], stream=0, check=False)
+        assert rc == B.INVALID_ARG, kw
+    # too small a destination for the library's own layout
+    assert B.gemm_pack_b_bf16(0, 16, 8, P, 8, P, packed_bytes=64 * 256 * 2 - 1, stream=0, check=False) == B.INVALID_ARG
+    # empty problems are no-ops
+    assert B.gemm_pack_b_bf16(0, 0, 8, 0, 8, 0, packed_bytes=0, stream=0, check=False) == B.OK
+    assert B.gemm_bf16_packed(0, 0, 8, 16, 0, 16, 0, 0.0, 0, 8, 0, stream=0, check=False) == B.OK
+    # misaligned image, bad epilogue flags, missing bias
+    assert B.gemm_bf16_packed(0, 4, 8, 16, P, 16, P + 2, 0.0, P, 8, 0, stream=0, check=False) == B.INVALID_ARG
+    assert B.gemm_bf16_packed(0, 4, 8, 16, P, 16, P, 0.0, P, 8, 0, epilogue=4, stream=0, check=False) == B.INVALID_ARG
+    assert B.gemm_bf16_packed(0, 4, 8, 16, P, 16, P, 0.0, P, 8, 0, epilogue=B.EPI_BIAS, stream=0,
+                              check=False) == B.INVALID_ARG
+    assert B.gemm_bf16_packed(0, 4, 8, 16, P, 15, P, 0.0, P, 8, 0, stream=0, check=False) == B.INVALID_ARG
