@@ -24,6 +24,11 @@ METRIC = "GEMM TFLOP/s and % of MFMA peak (fp32, bf16), 4096^3 and MLP shapes"
 PEAK_BF16 = 2516.6      # TFLOP/s, dense bf16 MFMA: 256 CUs x 4096 flop/clk x 2.4 GHz
 PEAK_F32 = 157.3        # TFLOP/s, fp32 MFMA
 HBM_TBS = 8.0
+# Bytes beyond L2 per launch of the headline kernel, from rocprofv3 --pmc FETCH_SIZE and
+# WRITE_SIZE passes over this same command (profiles/bf16_pingpong_256x256x64_gemm4096_nn.md):
+# (98408.1 KiB x 2.0 + 32768.0 KiB x 1.0) x 1024; the factors are what the same counters
+# read for a plain 1 GiB copy.  Valid for the kernel the counters were taken on only.
+HEADLINE_TRAFFIC = {"bf16_pingpong_256x256x64": (98408.1 * 2.0 + 32768.0 * 1.0) * 1024.0}
 
 
 def main():
@@ -135,7 +140,8 @@ def main():
         "config": {"workload": "bf16-in/fp32-acc/bf16-out GEMM M=N=K=4096 row-major (NN) beta=0, N(0,1) inputs",
                    "variant": variant, "split": split},
         "roofline": {"bound": "mfma", "achieved": round(achieved, 2), "peak": PEAK_BF16, "unit": "TFLOP/s",
-                     "frac": round(achieved / PEAK_BF16, 4), "traffic": None,
+                     "frac": round(achieved / PEAK_BF16, 4), "traffic": HEADLINE_TRAFFIC.get(variant),
+                     "traffic_unit": "bytes per launch (algorithmic: %d)" % (2 * (M * K + K * N + M * N)),
                      "kernel": variant, "us_per_launch": round(ev * 1e6, 2),
                      "us_median": round(med * 1e6, 2), "us_min": round(mn * 1e6, 2),
                      "frac_of_measured_mfma_rate": round(achieved / measured["bf16_normal_operands"], 4)},
