@@ -10,7 +10,7 @@
 // 64 B/clk of the vector memory path), and the 64 loads a k-block needs occupy
 // that unit for about half of the block's MFMA time.  With one wave per SIMD that
 // time is lost to the matrix pipe; here one wave of each SIMD issues loads and LDS
-// fragment reads ("memory phase") while the other issues nothing but its 32 MFMAs
+// fragment reads ("memory phase") while the other issues nothing but its 64 MFMAs
 // ("compute phase"), and a workgroup barrier swaps the roles.  Waves 4-7 run the
 // same sequence one phase behind waves 0-3.  It is the software pipelining of
 // operand re-layout against the matrix instruction that the paper applies to its
@@ -29,7 +29,7 @@ namespace {
 
 constexpr int PP_BM = 256, PP_BN = 256, PP_NW = 8;
 constexpr int PP_WM = 128, PP_WN = 64;          // wave tile
-constexpr int PP_TM = PP_WM / 32, PP_TN = PP_WN / 32;
+constexpr int PP_TM = PP_WM / 16, PP_TN = PP_WN / 16;     // 16x16 MFMA tiles per wave tile: 8 x 4
 constexpr uint32_t PP_A_BYTES = PP_BM * BK * 2, PP_B_BYTES = PP_BN * BK * 2;
 constexpr uint32_t PP_SLOT = 32768;              // one half-block (A or B part of a k-block)
 constexpr int PP_SLOTS = 5;
@@ -143,21 +143,20 @@ __device__ __forceinline__ void pp_body(const Bf16Args &p)
         advance_loads();
     };
 
-    f32x16 acc[PP_TN][PP_TM];
+    f32x4 acc[PP_TN][PP_TM];
 #pragma unroll
     for (int a = 0; a < PP_TN; ++a)
 #pragma unroll
         for (int b = 0; b < PP_TM; ++b)
-#pragma unroll
-            for (int r = 0; r < 16; ++r)
-                acc[a][b][r] = 0.0f;
+            acc[a][b] = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
 
-    // Memory phase: every fragment of one k-block (4 slices of 16; 24 fragments) into
-    // registers, and - when `request` - this wave's 8 loads of a later half-block, one
-    // after every third fragment read so that the LDS reads complete while the wave
-    // is held by the address unit.  The loads only write slots nobody reads in this
-    // phase, so their order relative to the reads does not matter for correctness.
-    bf16x8 fa[4][PP_TM], fb[4][PP_TN];
+    // Memory phase: every fragment of one k-block (2 steps of 32 k; 8 + 4 fragments
+    // each) into registers, and - when `request` - this wave's 8 loads of a later
+    // half-block, one after every third fragment read so that the LDS reads complete
+    // while the wave is held by the address unit.  The loads only write slots nobody
+    // reads in this phase, so their order relative to the reads does not matter for
+    // correctness.
+    bf16x8 fa[2][PP_TM], fb[2][PP_TN];
     int rd_slot = 0;                            // slot of A(t); B(t) is the next one
     auto memory_phase = [&](bool request) {
         LDS_AS char *at = smem + (uint32_t)rd_slot * PP_SLOT;
@@ -166,11 +165,11 @@ __device__ __forceinline__ void pp_body(const Bf16Args &p)
             constexpr int j = decltype(jc)::value;
             static_for<0, 3>([&](auto ic) {
                 constexpr int id = 3 * j + decltype(ic)::value;
-                constexpr int sl = id / (PP_TM + PP_TN), q = id % (PP_TM + PP_TN);
+                constexpr int st = id / (PP_TM + PP_TN), q = id % (PP_TM + PP_TN);
                 if constexpr (q < PP_TM)
-                    fa[sl][q] = ATile::read_frag(at, wm * PP_WM, q, sl, lane);
+                    fa[st][q] = ATile::read_frag16(at, wm * PP_WM, q, st, lane);
                 else
-                    fb[sl][q - PP_TM] = BTile::read_frag(bt, wn * PP_WN, q - PP_TM, sl, lane);
+                    fb[st][q - PP_TM] = BTile::read_frag16(bt, wn * PP_WN, q - PP_TM, st, lane);
             });
             if (request)
                 issue_one(j);
@@ -179,17 +178,20 @@ __device__ __forceinline__ void pp_body(const Bf16Args &p)
         if (request)
             advance_loads();
     };
-    // Compute phase: 32 MFMAs.  Operands are passed swapped (B fragment first) so the
-    // 32x32 result is C^T: lane l owns row m = l%32 and 4 consecutive columns per
-    // group of 4 registers.
+    // Compute phase: 64 x v_mfma_f32_16x16x32_bf16 (the same 1024 matrix-pipe cycles as
+    // 32 of the 32x32x16 form, but each accumulator register is read and written half as
+    // often per flop: on random operands the register-only issue loop sustains ~15 %
+    // more with this shape, and the chip is power-limited).  Operands are passed swapped
+    // (B fragment first) so the 16x16 result is C^T: lane l owns row m = l%16 and the 4
+    // consecutive columns 4*(l/16) .. +3.
     auto compute_block = [&]() {
 #pragma unroll
-        for (int s = 0; s < 4; ++s)
+        for (int st = 0; st < 2; ++st)
 #pragma unroll
             for (int a = 0; a < PP_TN; ++a)
 #pragma unroll
                 for (int b = 0; b < PP_TM; ++b)
-                    acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[s][a], fa[s][b], acc[a][b], 0, 0, 0);
+                    acc[a][b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fb[st][a], fa[st][b], acc[a][b], 0, 0, 0);
     };
 
     if (n_iter > 0) {
@@ -231,9 +233,9 @@ __device__ __forceinline__ void pp_body(const Bf16Args &p)
             phase_sync();
     }
 
-    // ---- epilogue.  Each wave stages 32 rows x 64 columns of its tile at a time in
-    // its own 8.5 KiB of LDS (all stages are free now), reads them back row-wise and
-    // stores 4 rows x 64 columns per instruction: full cache lines for both output types.
+    // ---- epilogue.  Each wave stages 32 rows x 64 columns of its tile at a time (two
+    // rows of 16x16 accumulators) in its own 8.5 KiB of LDS (all stages are free now),
+    // reads them back row-wise and stores 4 or 8 rows x whole cache lines per instruction.
     LDS_AS float *stage_f = (LDS_AS float *)(smem + (uint32_t)w * (32 * PP_EPI_LD * 4));
     const bool to_partial = p.split > 1;
     float *part = to_partial ? p.partial + (int64_t)blockIdx.y * p.M * p.N : nullptr;
@@ -248,15 +250,16 @@ __device__ __forceinline__ void pp_body(const Bf16Args &p)
     if (fast_bf16) {
         LDS_AS char *stage_h = smem + (uint32_t)w * (32 * 136);
         uint16_t *crow = (uint16_t *)p.epi.C + (m0 + wm * PP_WM) * p.epi.ldc + n0 + wn * PP_WN;
-        static_for<0, PP_TM>([&](auto bc) {
-            constexpr int b = decltype(bc)::value;
+        static_for<0, PP_TM / 2>([&](auto bc) {
+            constexpr int b2 = decltype(bc)::value;
             asm volatile("" ::: "memory");
-            static_for<0, PP_TN * 4>([&](auto aq) {
-                constexpr int a = decltype(aq)::value / 4, q = decltype(aq)::value % 4;
-                const int col = a * 32 + 8 * q + 4 * (lane >> 5);
-                const u32x2 pk = {pack_bf16x2(acc[a][b][4 * q + 0], acc[a][b][4 * q + 1]),
-                                  pack_bf16x2(acc[a][b][4 * q + 2], acc[a][b][4 * q + 3])};
-                *(LDS_AS u32x2 *)(stage_h + (lane & 31) * 136 + col * 2) = pk;
+            static_for<0, 2 * PP_TN>([&](auto aq) {
+                constexpr int bb = decltype(aq)::value / PP_TN, a = decltype(aq)::value % PP_TN;
+                const int row = 16 * bb + (lane & 15);
+                const int col = 16 * a + 4 * (lane >> 4);
+                const f32x4 v = acc[a][2 * b2 + bb];
+                const u32x2 pk = {pack_bf16x2(v[0], v[1]), pack_bf16x2(v[2], v[3])};
+                *(LDS_AS u32x2 *)(stage_h + row * 136 + col * 2) = pk;
             });
             asm volatile("" ::: "memory");
             __builtin_amdgcn_wave_barrier();
@@ -267,21 +270,20 @@ __device__ __forceinline__ void pp_body(const Bf16Args &p)
                 // 136-byte pitch keeps rows 8-byte aligned only: two 64-bit reads
                 const u32x2 lo = *(LDS_AS u32x2 *)(stage_h + row * 136 + c8 * 16);
                 const u32x2 hi = *(LDS_AS u32x2 *)(stage_h + row * 136 + c8 * 16 + 8);
-                if (m0 + wm * PP_WM + b * 32 + row < p.M)
-                    *(u32x4 *)(crow + (int64_t)(b * 32 + row) * p.epi.ldc + c8 * 8) = u32x4{lo[0], lo[1], hi[0], hi[1]};
+                if (m0 + wm * PP_WM + b2 * 32 + row < p.M)
+                    *(u32x4 *)(crow + (int64_t)(b2 * 32 + row) * p.epi.ldc + c8 * 8) = u32x4{lo[0], lo[1], hi[0], hi[1]};
             }
             __builtin_amdgcn_wave_barrier();
         });
         return;
     }
-    static_for<0, PP_TM>([&](auto bc) {
-        constexpr int b = decltype(bc)::value;
+    static_for<0, PP_TM / 2>([&](auto bc) {
+        constexpr int b2 = decltype(bc)::value;
         asm volatile("" ::: "memory");
-        static_for<0, PP_TN * 4>([&](auto aq) {
-            constexpr int a = decltype(aq)::value / 4, q = decltype(aq)::value % 4;
-            const int col = a * 32 + 8 * q + 4 * (lane >> 5);
-            *(LDS_AS f32x4 *)(stage_f + (lane & 31) * PP_EPI_LD + col) =
-                f32x4{acc[a][b][4 * q + 0], acc[a][b][4 * q + 1], acc[a][b][4 * q + 2], acc[a][b][4 * q + 3]};
+        static_for<0, 2 * PP_TN>([&](auto aq) {
+            constexpr int bb = decltype(aq)::value / PP_TN, a = decltype(aq)::value % PP_TN;
+            *(LDS_AS f32x4 *)(stage_f + (16 * bb + (lane & 15)) * PP_EPI_LD + 16 * a + 4 * (lane >> 4)) =
+                acc[a][2 * b2 + bb];
         });
         asm volatile("" ::: "memory");
         __builtin_amdgcn_wave_barrier();
@@ -290,7 +292,7 @@ __device__ __forceinline__ void pp_body(const Bf16Args &p)
             const int idx = i * 64 + lane;
             const int row = idx >> 4, c4 = idx & 15;
             const f32x4 v = *(LDS_AS f32x4 *)(stage_f + row * PP_EPI_LD + c4 * 4);
-            const int64_t m = m0 + wm * PP_WM + b * 32 + row;
+            const int64_t m = m0 + wm * PP_WM + b2 * 32 + row;
             const int64_t n = n0 + wn * PP_WN + c4 * 4;
             if (m < p.M) {
                 if (to_partial)

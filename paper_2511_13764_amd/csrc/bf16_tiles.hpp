@@ -161,6 +161,14 @@ struct KMajorTile {
     {
         return *(LDS_AS bf16x8 *)(tile + frag_byte(row_base, t, ks, lane));
     }
+    // Operand of v_mfma_f32_16x16x32_bf16 for 16-row tile t and 32-deep k-step s: lane l
+    // holds row t*16 + l%16 and the 8 k-values of chunk 4*s + l/16.
+    __device__ static bf16x8 read_frag16(LDS_AS char *tile, int row_base, int t, int s, int lane)
+    {
+        const int r = row_base + t * 16 + (lane & 15);
+        const int c = 4 * s + (lane >> 4);
+        return *(LDS_AS bf16x8 *)(tile + (uint32_t)(r * 128 + ((c ^ ((r >> 1) & 7)) << 4)));
+    }
 };
 
 // ---------------------------------------------------------------------------
@@ -241,6 +249,25 @@ struct MNMajorTile {
         s16x8 r = __builtin_shufflevector(v[0], v[1], 0, 1, 2, 3, 4, 5, 6, 7);
         return __builtin_bit_cast(bf16x8, r);
     }
+    // Operand of v_mfma_f32_16x16x32_bf16 for 16-column tile t and 32-deep k-step s:
+    // block b of 16 lanes holds k = 8*b .. 8*b+7 of the step for column t*16 + lane%16,
+    // i.e. two transposing reads of k-rows 32*s + 8*b + 4*rd + 0..3.
+    __device__ static bf16x8 read_frag16(LDS_AS char *tile, int col_base, int t, int s, int lane)
+    {
+        const int b = lane >> 4, i = lane & 15;
+        const int col = col_base + t * 16 + 4 * (i & 3);
+        const int c = col >> 3;
+        const int within = (col & 7) * 2;
+        s16x4 v[2];
+#pragma unroll
+        for (int rd = 0; rd < 2; ++rd) {
+            const int kr = s * 32 + 8 * b + 4 * rd + (i >> 2);
+            const uint32_t byte = (uint32_t)(kr * kRowBytes + ((c ^ ((kr & 3) << 2)) << 4) + within);
+            v[rd] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((LDS_AS s16x4 *)(tile + byte));
+        }
+        s16x8 r = __builtin_shufflevector(v[0], v[1], 0, 1, 2, 3, 4, 5, 6, 7);
+        return __builtin_bit_cast(bf16x8, r);
+    }
 };
 
 // ---------------------------------------------------------------------------
@@ -278,6 +305,12 @@ struct PackedTile {
     {
         const int kg = 2 * ks + (lane >> 5);
         const int col = col_base + t * 32 + (lane & 31);
+        return *(LDS_AS bf16x8 *)(tile + (uint32_t)(kg * COLS + col) * 16u);
+    }
+    __device__ static bf16x8 read_frag16(LDS_AS char *tile, int col_base, int t, int s, int lane)
+    {
+        const int kg = 4 * s + (lane >> 4);
+        const int col = col_base + t * 16 + (lane & 15);
         return *(LDS_AS bf16x8 *)(tile + (uint32_t)(kg * COLS + col) * 16u);
     }
 };
