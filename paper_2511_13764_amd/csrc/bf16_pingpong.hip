@@ -83,9 +83,9 @@ __device__ __forceinline__ void pp_body(const Bf16Args &p)
     const int it_end = (it_begin + per < total) ? it_begin + per : total;
     const int n_iter = it_end - it_begin;
 
-    // This wave's operand (A for waves 4-7, B for waves 0-3).  Wave-load g = 8*wl + j of
-    // a half-block is addressed as scalar base + g * stride + a 32-bit lane offset that
-    // only depends on the parity of g (two registers for the whole kernel).
+    // This wave's operand (A for waves 4-7, B for waves 0-3).  A wave-load g of a
+    // half-block is addressed as scalar base + a scalar offset of g + a 32-bit lane
+    // offset that only depends on the parity of g (two registers for the whole kernel).
     const uint16_t *op_base = group ? p.A : p.B;
     const int64_t *op_off = group ? p.A_off : p.B_off;
     const int64_t op_ld = group ? p.lda : p.ldb;
@@ -93,8 +93,17 @@ __device__ __forceinline__ void pp_body(const Bf16Args &p)
     const int64_t op_limit = group ? p.M : p.N;
     const int64_t op_origin = group ? ATile::origin(m0, p.lda) : BTile::origin(n0, p.ldb);
     const int64_t op_kstep = group ? ATile::kstep(p.lda) : BTile::kstep(p.ldb);
-    const uint32_t lane_off0 = group ? ATile::lane_off_bytes(0, lane, op_ld) : BTile::lane_off_bytes(0, lane, op_ld);
-    const uint32_t lane_off1 = group ? ATile::lane_off_bytes(1, lane, op_ld) : BTile::lane_off_bytes(1, lane, op_ld);
+    // Wave-load g of a half-block (32 of them) is taken by loader wave wl as its j-th:
+    //   g = (j & 3) | ((wl & 1) << 2) | ((2 * (wl >> 1) + (j >> 2)) << 3),
+    // so bit 2 of g is the same for all 8 loads of a wave.  For an m/n-contiguous
+    // operand that bit selects the second swizzle term (+-32 bytes per lane), which can
+    // then be folded into the two lane offsets once instead of costing a register and
+    // an add per load.
+    const int g_fixed = (wl & 1) << 2;
+    const int32_t fold = (group ? ATile::delta_applies(g_fixed) : BTile::delta_applies(g_fixed))
+                             ? (group ? ATile::lane_delta_bytes(lane) : BTile::lane_delta_bytes(lane)) : 0;
+    const uint32_t lane_off0 = (group ? ATile::lane_off_bytes(0, lane, op_ld) : BTile::lane_off_bytes(0, lane, op_ld)) + (uint32_t)fold;
+    const uint32_t lane_off1 = (group ? ATile::lane_off_bytes(1, lane, op_ld) : BTile::lane_off_bytes(1, lane, op_ld)) + (uint32_t)fold;
 
     // Load cursor of this wave's operand: next block's (batch index, k-block), its
     // source pointer and its ring slot.  Half-block 2t is A(t), 2t+1 is B(t); slot = index % 5.
@@ -105,7 +114,7 @@ __device__ __forceinline__ void pp_body(const Bf16Args &p)
 
     // One of the 8 wave-loads of this wave's next half-block.
     auto issue_one = [&](int j) {
-        const int gi = wl * 8 + j;
+        const int gi = (j & 3) | g_fixed | ((2 * (wl >> 1) + (j >> 2)) << 3);
         const char *gj = (const char *)ld_ptr + (group ? ATile::instr_offset_bytes(gi, op_ld)
                                                        : BTile::instr_offset_bytes(gi, op_ld));
         const uint32_t off = (j & 1) ? lane_off1 : lane_off0;

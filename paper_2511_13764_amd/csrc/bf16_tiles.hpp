@@ -144,6 +144,8 @@ struct KMajorTile {
         const int c = (lane & 7) ^ ((4 * parity + (lane >> 4)) & 7);
         return (uint32_t)(((int64_t)(lane >> 3) * ld + 8 * c) * 2);
     }
+    __device__ static int32_t lane_delta_bytes(int) { return 0; }
+    __device__ static bool delta_applies(int) { return false; }
     __device__ static bool lane_valid(int g, int lane, int64_t row0, int64_t row_limit)
     {
         return row0 + 8 * g + (lane >> 3) < row_limit;
@@ -174,8 +176,11 @@ struct KMajorTile {
 // ---------------------------------------------------------------------------
 // Operand tile whose contiguous direction is m or n ("MN-major": A with
 // transA == 1, B with transB == 0).  LDS image: k-row kr takes COLS*2 bytes; its
-// 16-byte chunk c (8 consecutive m/n) sits at chunk position c ^ ((kr & 3) << 2),
-// which spreads the four k-rows one transposing read touches over distinct banks.
+// 16-byte chunk c (8 consecutive m/n) sits at chunk position c ^ swz(kr) with
+// swz(kr) = ((kr & 3) << 2) | (((kr >> 3) & 1) << 1).  The first term spreads the
+// four k-rows one transposing read touches over distinct banks; the second keeps
+// k-rows kr and kr + 8, which the two 16-lane blocks of a half-wave read for the
+// 16x16x32 MFMA operand, 32 bytes apart.
 // ---------------------------------------------------------------------------
 template <int COLS, int NW>
 struct MNMajorTile {
@@ -184,12 +189,14 @@ struct MNMajorTile {
     static constexpr int kInstr = BK * kChunksPerRow / 64;
     static constexpr int kPerWave = kInstr / NW;
 
+    __device__ static int swz(int kr) { return ((kr & 3) << 2) | (((kr >> 3) & 1) << 1); }
+
     __device__ static int64_t src_offset(int w, int j, int lane, int64_t col0, int64_t col_limit, int64_t ld)
     {
         const int idx = (w * kPerWave + j) * 64 + lane;
         const int kr = idx / kChunksPerRow;
         const int pc = idx % kChunksPerRow;
-        const int c = pc ^ ((kr & 3) << 2);
+        const int c = pc ^ swz(kr);
         int64_t col = col0 + 8 * c;
         col = col < col_limit ? col : col0;           // chunk wholly outside: any valid chunk
         return (int64_t)kr * ld + col;
@@ -200,32 +207,32 @@ struct MNMajorTile {
         const int idx = (w * kPerWave + j) * 64 + lane;
         const int kr = idx / kChunksPerRow;
         const int pc = idx % kChunksPerRow;
-        const int c = pc ^ ((kr & 3) << 2);
+        const int c = pc ^ swz(kr);
         const int64_t rel = (col0 + 8 * c < col_limit) ? 8 * c : 0;
         return (uint32_t)(((int64_t)kr * ld + rel) * 2);
     }
 
-    // Scalar-base form: wave-instruction g reads k-rows (64/kChunksPerRow)*g.. ; the
-    // swizzle term depends on g only through its parity when a row is 32 chunks wide.
-    static_assert(kChunksPerRow == 32 || kChunksPerRow == 16, "row of 256 or 128 elements");
+    // Scalar-base form: wave-load g covers 2 (256-column tile) or 4 (128) k-rows.  The
+    // lane offset depends on g through its parity (first swizzle term, 256 columns
+    // only) and through bit 3 of its k-rows (second term), which moves the chunk by
+    // +-32 bytes: offset = lane_off_bytes(g & 1) + (delta_applies(g) ? lane_delta_bytes : 0).
     __device__ static int64_t instr_offset_bytes(int g, int64_t ld) { return (int64_t)g * (64 / kChunksPerRow) * ld * 2; }
     __device__ static int64_t origin(int64_t first, int64_t) { return first; }
     __device__ static int64_t kstep(int64_t ld) { return (int64_t)BK * ld; }
     __device__ static uint32_t lane_off_bytes(int parity, int lane, int64_t ld)
     {
-        // rows per instruction: 2 (32 chunks/row) or 4 (16 chunks/row)
+        static_assert(kChunksPerRow == 32 || kChunksPerRow == 16, "row of 256 or 128 elements");
         const int kr_in = lane / kChunksPerRow;
         const int pc = lane % kChunksPerRow;
-        const int kr_low = kChunksPerRow == 32 ? ((2 * parity + kr_in) & 3) : (kr_in & 3);
-        const int c = pc ^ (kr_low << 2);
+        const int c = pc ^ ((((64 / kChunksPerRow) * parity + kr_in) & 3) << 2);
         return (uint32_t)(((int64_t)kr_in * ld + 8 * c) * 2);
     }
+    __device__ static int32_t lane_delta_bytes(int lane) { return ((lane % kChunksPerRow) & 2) ? -32 : 32; }
+    __device__ static bool delta_applies(int g) { return (((64 / kChunksPerRow) * g) >> 3) & 1; }
     __device__ static bool lane_valid(int g, int lane, int64_t col0, int64_t col_limit)
     {
-        const int kr_in = lane / kChunksPerRow;
-        const int pc = lane % kChunksPerRow;
-        const int kr_low = kChunksPerRow == 32 ? ((2 * (g & 1) + kr_in) & 3) : (kr_in & 3);
-        const int c = pc ^ (kr_low << 2);
+        const int kr = (64 / kChunksPerRow) * g + lane / kChunksPerRow;
+        const int c = (lane % kChunksPerRow) ^ swz(kr);
         return col0 + 8 * c < col_limit;
     }
 
@@ -243,7 +250,7 @@ struct MNMajorTile {
 #pragma unroll
         for (int rd = 0; rd < 2; ++rd) {
             const int kr = ks * 16 + 8 * (b >> 1) + 4 * rd + (i >> 2);
-            const uint32_t byte = (uint32_t)(kr * kRowBytes + ((c ^ ((kr & 3) << 2)) << 4) + within);
+            const uint32_t byte = (uint32_t)(kr * kRowBytes + ((c ^ swz(kr)) << 4) + within);
             v[rd] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((LDS_AS s16x4 *)(tile + byte));
         }
         s16x8 r = __builtin_shufflevector(v[0], v[1], 0, 1, 2, 3, 4, 5, 6, 7);
@@ -262,7 +269,7 @@ struct MNMajorTile {
 #pragma unroll
         for (int rd = 0; rd < 2; ++rd) {
             const int kr = s * 32 + 8 * b + 4 * rd + (i >> 2);
-            const uint32_t byte = (uint32_t)(kr * kRowBytes + ((c ^ ((kr & 3) << 2)) << 4) + within);
+            const uint32_t byte = (uint32_t)(kr * kRowBytes + ((c ^ swz(kr)) << 4) + within);
             v[rd] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((LDS_AS s16x4 *)(tile + byte));
         }
         s16x8 r = __builtin_shufflevector(v[0], v[1], 0, 1, 2, 3, 4, 5, 6, 7);
@@ -300,6 +307,8 @@ struct PackedTile {
     __device__ static int64_t origin(int64_t first, int64_t) { return first * 8; }
     __device__ static int64_t kstep(int64_t ld) { return 8 * ld; }
     __device__ static uint32_t lane_off_bytes(int, int lane, int64_t) { return (uint32_t)lane * 16u; }
+    __device__ static int32_t lane_delta_bytes(int) { return 0; }
+    __device__ static bool delta_applies(int) { return false; }
     __device__ static bool lane_valid(int, int, int64_t, int64_t) { return true; }
     __device__ static bf16x8 read_frag(LDS_AS char *tile, int col_base, int t, int ks, int lane)
     {
