@@ -397,10 +397,7 @@ static hipError_t launch_pp(const Problem &p)
 
 hipError_t launch_bf16_pingpong(const Problem &p) { return launch_pp(p); }
 
-// Same alignment rules as the 4-wave kernels, plus 32-bit lane offsets.
-bool bf16_pingpong_eligible(const Problem &p)
-{
-    return bf16_mfma_eligible(p) && p.lda < (1 << 22) && p.ldb < (1 << 22);
-}
+// Same alignment rules as the 4-wave kernel (which include the 32-bit lane offsets).
+bool bf16_pingpong_eligible(const Problem &p) { return bf16_mfma_eligible(p); }
 
 }  // namespace brg

@@ -31,7 +31,7 @@ bf16_stream_kernel(Bf16Args p)
     typedef typename TileOf<ST_BN, 4, B_LAY>::type BTile;
     constexpr int WGM = BM == 128 ? 2 : 1, WGN = 4 / WGM;     // wave grid
     constexpr int WM = BM / WGM, WN = ST_BN / WGN;
-    constexpr int TM = WM / 32, TN = WN / 32;
+    constexpr int TM = WM / 16, TN = WN / 16;                 // 16x16 MFMA tiles per wave
     constexpr uint32_t A_BYTES = BM * BK * 2, B_BYTES = ST_BN * BK * 2;
     constexpr uint32_t STAGE = A_BYTES + B_BYTES;
     constexpr int L = ATile::kPerWave + BTile::kPerWave;        // loads per wave per block
@@ -83,14 +83,12 @@ bf16_stream_kernel(Bf16Args p)
         ld_b += b_kstep;
         ld_slot = ld_slot + 1 == stages ? 0 : ld_slot + 1;
     };
-    f32x16 acc[TN][TM];
+    f32x4 acc[TN][TM];
 #pragma unroll
     for (int a = 0; a < TN; ++a)
 #pragma unroll
         for (int b = 0; b < TM; ++b)
-#pragma unroll
-            for (int r = 0; r < 16; ++r)
-                acc[a][b][r] = 0.0f;
+            acc[a][b] = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
 
     const int ahead = stages - 1;
     for (int s = 0; s < ahead && s < n_iter; ++s)
@@ -108,30 +106,30 @@ bf16_stream_kernel(Bf16Args p)
             issue_loads();                          // into the slot read in iteration t - 1
         LDS_AS char *at = smem + (uint32_t)rd_slot * STAGE;
         LDS_AS char *bt = at + A_BYTES;
-        bf16x8 fa[4][TM], fb[4][TN];
+        bf16x8 fa[2][TM], fb[2][TN];
 #pragma unroll
-        for (int ks = 0; ks < 4; ++ks) {
+        for (int st = 0; st < 2; ++st) {
 #pragma unroll
             for (int i = 0; i < TM; ++i)
-                fa[ks][i] = ATile::read_frag(at, wm * WM, i, ks, lane);
+                fa[st][i] = ATile::read_frag16(at, wm * WM, i, st, lane);
 #pragma unroll
             for (int i = 0; i < TN; ++i)
-                fb[ks][i] = BTile::read_frag(bt, wn * WN, i, ks, lane);
+                fb[st][i] = BTile::read_frag16(bt, wn * WN, i, st, lane);
         }
 #pragma unroll
-        for (int ks = 0; ks < 4; ++ks)
+        for (int st = 0; st < 2; ++st)
 #pragma unroll
             for (int a = 0; a < TN; ++a)
 #pragma unroll
                 for (int b = 0; b < TM; ++b)
-                    acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[ks][a], fa[ks][b], acc[a][b], 0, 0, 0);
+                    acc[a][b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fb[st][a], fa[st][b], acc[a][b], 0, 0, 0);
         // The fragments are in registers before the next barrier lets another wave's
         // loads overwrite this slot.
         wait_lgkmcnt0();
         rd_slot = rd_slot + 1 == stages ? 0 : rd_slot + 1;
     }
 
-    store_wave_tile<TM, TN>(p, acc, m0 + wm * WM + (lane & 31), n0 + wn * WN + 4 * (lane >> 5), (int)blockIdx.y);
+    store_wave_tile16<TM, TN>(p, acc, m0 + wm * WM + (lane & 15), n0 + wn * WN + 4 * (lane >> 4), (int)blockIdx.y);
 }
 
 template <int BM>

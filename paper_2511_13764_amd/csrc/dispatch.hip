@@ -8,7 +8,6 @@ const char *variant_name(int v)
 {
     switch (v) {
     case V_GENERIC: return "generic_64x64x16_f32mfma";
-    case V_BF16_256x256: return "bf16_256x256x64";
     case V_BF16_128x128: return "bf16_128x128x64";
     case V_BF16_PP256: return "bf16_pingpong_256x256x64";
     case V_F32_128x128: return "f32_128x128x32";
@@ -23,7 +22,6 @@ bool variant_eligible(int v, const Problem &p)
 {
     switch (v) {
     case V_GENERIC: return true;
-    case V_BF16_256x256:
     case V_BF16_128x128: return bf16_mfma_eligible(p);
     case V_BF16_PP256: return bf16_pingpong_eligible(p);
     case V_F32_128x128: return f32_mfma_eligible(p);
@@ -137,7 +135,7 @@ int choose_plan(const Problem &p, size_t workspace_bytes, int forced_variant, in
         // 512), 256x256 tiles beyond that (measured crossover on squares: 2816 -> 3072).
         const int64_t t128 = ((p.M + 127) / 128) * ((p.N + 127) / 128);
         if (t128 > 512) {
-            plan.variant = bf16_pingpong_eligible(p) ? V_BF16_PP256 : V_BF16_256x256;
+            plan.variant = V_BF16_PP256;
         } else {
             plan.variant = V_BF16_128x128;
             plan.split = split_for_small_grid(p, workspace_bytes);
@@ -165,7 +163,6 @@ hipError_t launch_variant(int v, const Problem &p)
 {
     switch (v) {
     case V_GENERIC: return launch_generic(p);
-    case V_BF16_256x256: return launch_bf16_256x256(p);
     case V_BF16_128x128: return launch_bf16_128x128(p);
     case V_BF16_PP256: return launch_bf16_pingpong(p);
     case V_F32_128x128: return launch_f32_128x128(p);

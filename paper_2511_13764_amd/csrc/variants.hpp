@@ -8,7 +8,6 @@ namespace brg {
 
 enum Variant {
     V_GENERIC = 0,      // any shape / alignment, fp32 MFMA, 64x64 tile
-    V_BF16_256x256,     // bf16, 256x256x64 workgroup tile, 128x128 wave tile
     V_BF16_128x128,     // bf16, 128x128x64 workgroup tile, 64x64 wave tile
     V_BF16_PP256,       // bf16, 256x256x64 tile, 8 waves in alternating memory/compute phases
     V_F32_128x128,      // fp32, 128x128x32 tile, fp32 MFMA
@@ -38,7 +37,6 @@ hipError_t launch_variant(int v, const Problem &p);
 
 // bf16_mfma.hip
 bool bf16_mfma_eligible(const Problem &p);
-hipError_t launch_bf16_256x256(const Problem &p);
 hipError_t launch_bf16_128x128(const Problem &p);
 // f32_mfma.hip
 bool f32_mfma_eligible(const Problem &p);
