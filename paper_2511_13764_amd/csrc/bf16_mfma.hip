@@ -5,9 +5,13 @@
 //   microkernel  = one workgroup (4 wavefronts) owning a BM x BN block of C,
 //                  fed from LDS in 64-deep k-blocks;
 //   nanokernel   = one wavefront's (BM/2) x (BN/2) register tile, built from
-//                  v_mfma_f32_16x16x32_bf16 and kept in registers for the whole
+//                  v_mfma_f32_32x32x16_bf16 and kept in registers for the whole
 //                  batch and K loops (no spills: a 64 x 64 wave tile takes 64
-//                  accumulator registers per lane).
+//                  accumulator registers per lane).  This latency-bound kernel keeps
+//                  the 32x32x16 form: with one wave per SIMD the four 16-deep slices
+//                  give a finer interleave of LDS reads and MFMAs than the 16x16x32
+//                  form, which measured 10-15 % slower here (it wins only where the
+//                  chip is power-limited, in the 8-wave kernel).
 //   "Flat" operands (Section 4.3): an operand whose contiguous direction is k
 //   feeds the matrix instruction with plain 128-bit LDS reads; one whose
 //   contiguous direction is m or n is re-laid-out on the way out of LDS with the
@@ -18,7 +22,7 @@
 // lane, no register staging).  One wave instruction fills 1 KiB of LDS in lane
 // order, so the swizzle that keeps the LDS reads bank-conflict free is applied by
 // choosing WHICH 16 global bytes each lane fetches.  Two LDS stages; the block
-// for k-step t+2 is requested while block t's second half is being multiplied.
+// for k-step t+2 is requested while block t's last slice is being multiplied.
 #include "bf16_tiles.hpp"
 
 namespace brg {
@@ -30,7 +34,7 @@ bf16_mfma_kernel(Bf16Args p)
     typedef typename TileOf<BM, 4, A_KMAJ>::type ATile;
     typedef typename TileOf<BN, 4, B_LAY>::type BTile;
     constexpr int WM = BM / 2, WN = BN / 2;         // wave tile
-    constexpr int TM = WM / 16, TN = WN / 16;       // 16x16 MFMA tiles per wave tile
+    constexpr int TM = WM / 32, TN = WN / 32;       // MFMA tiles per wave tile
     constexpr uint32_t A_BYTES = BM * BK * 2, B_BYTES = BN * BK * 2;
     constexpr uint32_t STAGE = A_BYTES + B_BYTES;
 
@@ -124,34 +128,35 @@ bf16_mfma_kernel(Bf16Args p)
         }
     };
 
-    f32x4 acc[TN][TM];
+    f32x16 acc[TN][TM];
 #pragma unroll
     for (int a = 0; a < TN; ++a)
 #pragma unroll
         for (int b = 0; b < TM; ++b)
-            acc[a][b] = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
+#pragma unroll
+            for (int r = 0; r < 16; ++r)
+                acc[a][b][r] = 0.0f;
 
-    // Fragments of one 32-deep k-step (v_mfma_f32_16x16x32_bf16), double-buffered.
     bf16x8 fa[2][TM], fb[2][TN];
-    auto read_frags = [&](int stage, int st, int buf) {
+    auto read_frags = [&](int stage, int ks, int buf) {
         LDS_AS char *at = smem + (uint32_t)stage * STAGE;
         LDS_AS char *bt = at + A_BYTES;
 #pragma unroll
         for (int t = 0; t < TM; ++t)
-            fa[buf][t] = ATile::read_frag16(at, wm * WM, t, st, lane);
+            fa[buf][t] = ATile::read_frag(at, wm * WM, t, ks, lane);
 #pragma unroll
         for (int t = 0; t < TN; ++t)
-            fb[buf][t] = BTile::read_frag16(bt, wn * WN, t, st, lane);
+            fb[buf][t] = BTile::read_frag(bt, wn * WN, t, ks, lane);
     };
-    // Operands are passed swapped (B fragment first) so that the 16x16 result tile is
-    // C^T: lane l then owns row m = l%16 and 4 consecutive columns n - which makes the
-    // epilogue's stores 8 or 16 bytes per lane.
+    // Operands are passed swapped (B fragment first) so that the 32x32 result tile is
+    // C^T: lane l then owns row m = l%32 and, per group of 4 registers, 4 consecutive
+    // columns n - which makes the epilogue's stores 8 or 16 bytes per lane.
     auto mma = [&](int buf) {
 #pragma unroll
         for (int a = 0; a < TN; ++a)
 #pragma unroll
             for (int b = 0; b < TM; ++b)
-                acc[a][b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fb[buf][a], fa[buf][b], acc[a][b], 0, 0, 0);
+                acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[buf][a], fa[buf][b], acc[a][b], 0, 0, 0);
     };
 
     if (n_iter > 0) {
@@ -164,14 +169,18 @@ bf16_mfma_kernel(Bf16Args p)
 
         // Steady state; the last block is peeled so that the loop body has no branch
         // around the barrier (the same peeling the paper applies to its pipelined
-        // packing loop).  Order inside one block: the first k-step multiplies while the
-        // second one's fragments are read; before the second is multiplied the barrier
-        // proves block it+1 complete and block `it` fully read, then the request for
-        // block it+2 and the first fragment reads of block it+1 are issued, and the
-        // second step's MFMAs cover their latency.
+        // packing loop).  Order inside one block: slices 0-2 multiply while the next
+        // slice's fragments are read; before slice 3 is multiplied the barrier proves
+        // block it+1 complete and block `it` fully read, then the request for block
+        // it+2 and the first fragment reads of block it+1 are issued, and slice 3's
+        // MFMAs cover their latency.
         for (int it = 0; it < n_iter - 1; ++it) {
             const int cur = it & 1;
             read_frags(cur, 1, 1);
+            mma(0);
+            read_frags(cur, 2, 0);
+            mma(1);
+            read_frags(cur, 3, 1);
             mma(0);
             wait_vmcnt0();
             wait_lgkmcnt0();
@@ -186,6 +195,10 @@ bf16_mfma_kernel(Bf16Args p)
             const int cur = (n_iter - 1) & 1;
             read_frags(cur, 1, 1);
             mma(0);
+            read_frags(cur, 2, 0);
+            mma(1);
+            read_frags(cur, 3, 1);
+            mma(0);
             mma(1);
         }
     }
@@ -193,7 +206,7 @@ bf16_mfma_kernel(Bf16Args p)
     // ---- epilogue: beta*C, bias, ReLU, narrowing, store (or raw partial for a split)
     // Every accumulator index below is a compile-time constant (static_for), so the
     // tile never leaves the register file.
-    store_wave_tile16<TM, TN>(p, acc, m0 + wm * WM + (lane & 15), n0 + wn * WN + 4 * (lane >> 4), (int)blockIdx.y);
+    store_wave_tile<TM, TN>(p, acc, m0 + wm * WM + (lane & 31), n0 + wn * WN + 4 * (lane >> 5), (int)blockIdx.y);
 }
 
 // ---------------------------------------------------------------------------

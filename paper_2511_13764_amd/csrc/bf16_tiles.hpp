@@ -430,6 +430,46 @@ __device__ __forceinline__ void store4_epilogue(const Epilogue &e, int64_t m, in
     }
 }
 
+// Store one wave's register tile (TN x TM accumulators of 32x32, computed with the
+// operands swapped so that lane l owns row l%32 and 4 consecutive columns per group
+// of 4 registers): raw fp32 partial sums for a split reduction, else the epilogue.
+// m_base / n_base: the row / first column this lane owns in accumulator (0, 0).
+template <int TM, int TN>
+__device__ __forceinline__ void store_wave_tile(const Bf16Args &p, f32x16 (&acc)[TN][TM], int64_t m_base,
+                                                int64_t n_base, int split_index)
+{
+    if (p.split > 1) {
+        float *part = p.partial + (int64_t)split_index * p.M * p.N;
+        const bool vec = (p.N & 3) == 0;
+        static_for<0, TM>([&](auto bc) {
+            constexpr int b = decltype(bc)::value;
+            const int64_t m = m_base + b * 32;
+            if (m < p.M) {
+                static_for<0, TN * 4>([&](auto aq) {
+                    constexpr int a = decltype(aq)::value / 4, q = decltype(aq)::value % 4;
+                    const int64_t n = n_base + a * 32 + q * 8;
+                    store4_partial(part + m * p.N + n, p.N - n, vec, acc[a][b][4 * q + 0], acc[a][b][4 * q + 1],
+                                   acc[a][b][4 * q + 2], acc[a][b][4 * q + 3]);
+                });
+            }
+        });
+    } else {
+        const bool vec = (p.epi.ldc & 3) == 0 && (((uintptr_t)p.epi.C) & 15) == 0;
+        static_for<0, TM>([&](auto bc) {
+            constexpr int b = decltype(bc)::value;
+            const int64_t m = m_base + b * 32;
+            if (m < p.M) {
+                static_for<0, TN * 4>([&](auto aq) {
+                    constexpr int a = decltype(aq)::value / 4, q = decltype(aq)::value % 4;
+                    const int64_t n = n_base + a * 32 + q * 8;
+                    store4_epilogue(p.epi, m, n, p.N - n, vec, acc[a][b][4 * q + 0], acc[a][b][4 * q + 1],
+                                    acc[a][b][4 * q + 2], acc[a][b][4 * q + 3]);
+                });
+            }
+        });
+    }
+}
+
 // Store one wave's register tile: TN x TM accumulators of 16x16 from
 // v_mfma_f32_16x16x32_bf16 with the operands swapped, so that lane l owns row l%16
 // and the 4 consecutive columns 4*(l/16) .. +3 of every accumulator.  Raw fp32 partial
