@@ -1,7 +1,9 @@
 // bf16 GEMM kernel for few rows of A (skinny M: the M = 16 / 128 shapes of an MLP
 // layer), where the time goes into streaming the B matrix from HBM once, not into the
 // matrix pipe - the regime the paper describes as bound by memory bandwidth
-// (Section 6, discussion of the flat-layout results).
+// (Section 6, discussion of the flat-layout results).  Its 128-row form also serves
+// grids of at most 256 tiles of 128 x 128 (one workgroup per CU anyway), where the
+// third stage hides the load latency that the two-stage 4-wave kernel exposes.
 //
 // A workgroup of 4 wavefronts owns a BM x 128 block of C (BM = 32, 64 or 128) and
 // walks its share of K in 64-deep blocks.  What matters here is how many bytes are
@@ -23,11 +25,12 @@ namespace {
 constexpr int ST_BN = 128;
 constexpr int ST_STAGES = 3;
 
-template <int BM, int B_LAY>
+template <int BM, bool A_KMAJ, int B_LAY>
 __global__ void __launch_bounds__(256)
 bf16_stream_kernel(Bf16Args p)
 {
-    typedef KMajorTile<BM, 4> ATile;
+    static_assert(A_KMAJ || BM == 128, "an m-contiguous A needs the 128-row tile");
+    typedef typename TileOf<BM, 4, A_KMAJ ? LAY_K : LAY_MN>::type ATile;
     typedef typename TileOf<ST_BN, 4, B_LAY>::type BTile;
     constexpr int WGM = BM == 128 ? 2 : 1, WGN = 4 / WGM;     // wave grid
     constexpr int WM = BM / WGM, WN = ST_BN / WGN;
@@ -66,7 +69,8 @@ bf16_stream_kernel(Bf16Args p)
     for (int j = 0; j < BTile::kPerWave; ++j)
         b_src[j] = BTile::src_rel_bytes(w, j, lane, n0, p.N, p.ldb);
     const int64_t b_kstep = BTile::kstep(p.ldb);
-    const uint16_t *ld_a = uniform_ptr(p.A + m0 * p.lda + (int64_t)it_begin * BK);
+    const int64_t a_kstep = ATile::kstep(p.lda);
+    const uint16_t *ld_a = uniform_ptr(p.A + ATile::origin(m0, p.lda) + (int64_t)it_begin * a_kstep);
     const uint16_t *ld_b = uniform_ptr(p.B + BTile::origin(n0, p.ldb) + (int64_t)it_begin * b_kstep);
     int ld_slot = 0;
 
@@ -79,7 +83,7 @@ bf16_stream_kernel(Bf16Args p)
 #pragma unroll
         for (int j = 0; j < ATile::kPerWave; ++j)
             load16_to_lds_saddr((const char *)ld_a, a_src[j], (uint32_t)(size_t)(smem + base + ATile::dst_byte(w, j)));
-        ld_a += BK;
+        ld_a += a_kstep;
         ld_b += b_kstep;
         ld_slot = ld_slot + 1 == stages ? 0 : ld_slot + 1;
     };
@@ -146,9 +150,16 @@ hipError_t launch_stream(const Problem &p)
     a.tiles_n = (int)((p.N + ST_BN - 1) / ST_BN);
     const dim3 grid((unsigned)(a.tiles_m * a.tiles_n), (unsigned)p.split);
     const size_t lds = (size_t)ST_STAGES * (BM + ST_BN) * BK * 2;
-    void (*kern)(Bf16Args) = p.b_packed ? bf16_stream_kernel<BM, LAY_PACKED>
-                             : p.transB == 1 ? bf16_stream_kernel<BM, LAY_K> : bf16_stream_kernel<BM, LAY_MN>;
-    static thread_local const void *configured[3] = {nullptr};
+    void (*kern)(Bf16Args) = p.b_packed ? bf16_stream_kernel<BM, true, LAY_PACKED>
+                             : p.transB == 1 ? bf16_stream_kernel<BM, true, LAY_K> : bf16_stream_kernel<BM, true, LAY_MN>;
+    if constexpr (BM == 128) {
+        if (p.transA == 1)
+            kern = p.b_packed ? bf16_stream_kernel<BM, false, LAY_PACKED>
+                   : p.transB == 1 ? bf16_stream_kernel<BM, false, LAY_K> : bf16_stream_kernel<BM, false, LAY_MN>;
+    } else if (p.transA == 1) {
+        return hipErrorInvalidValue;
+    }
+    static thread_local const void *configured[6] = {nullptr};
     bool done = false;
     for (const void *c : configured)
         done = done || c == (const void *)kern;
@@ -175,10 +186,11 @@ hipError_t launch_bf16_stream(const Problem &p, int bm)
     }
 }
 
-// Plain GEMM with A stored M x K (k contiguous); B in either order.
-bool bf16_stream_eligible(const Problem &p)
+// Plain GEMM; the 32- and 64-row tiles need A stored M x K (k contiguous), the 128-row
+// tile takes either order; B in any layout.
+bool bf16_stream_eligible(const Problem &p, int bm)
 {
-    return bf16_mfma_eligible(p) && p.transA == 0 && p.batch == 1 && !p.A_off && !p.B_off;
+    return bf16_mfma_eligible(p) && (p.transA == 0 || bm == 128) && p.batch == 1 && !p.A_off && !p.B_off;
 }
 
 }  // namespace brg

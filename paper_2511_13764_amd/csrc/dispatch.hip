@@ -25,9 +25,9 @@ bool variant_eligible(int v, const Problem &p)
     case V_BF16_128x128: return bf16_mfma_eligible(p);
     case V_BF16_PP256: return bf16_pingpong_eligible(p);
     case V_F32_128x128: return f32_mfma_eligible(p);
-    case V_BF16_STREAM32:
-    case V_BF16_STREAM64:
-    case V_BF16_STREAM128: return bf16_stream_eligible(p);
+    case V_BF16_STREAM32: return bf16_stream_eligible(p, 32);
+    case V_BF16_STREAM64: return bf16_stream_eligible(p, 64);
+    case V_BF16_STREAM128: return bf16_stream_eligible(p, 128);
     default: return false;
     }
 }
@@ -125,11 +125,11 @@ static int split_for_f32(const Problem &p, size_t workspace_bytes)
 int choose_plan(const Problem &p, size_t workspace_bytes, int forced_variant, int forced_split, Plan *out)
 {
     Plan plan{V_GENERIC, 1};
-    if (p.M <= 128 && bf16_stream_eligible(p)) {
+    const int skinny_bm = p.M <= 32 ? 32 : p.M <= 64 ? 64 : 128;
+    if (p.M <= 128 && bf16_stream_eligible(p, skinny_bm)) {
         // Few rows of A: the time goes into streaming B once.
-        const int bm = p.M <= 32 ? 32 : p.M <= 64 ? 64 : 128;
-        plan.variant = bm == 32 ? V_BF16_STREAM32 : bm == 64 ? V_BF16_STREAM64 : V_BF16_STREAM128;
-        plan.split = split_for_stream(p, bm, workspace_bytes);
+        plan.variant = skinny_bm == 32 ? V_BF16_STREAM32 : skinny_bm == 64 ? V_BF16_STREAM64 : V_BF16_STREAM128;
+        plan.split = split_for_stream(p, skinny_bm, workspace_bytes);
     } else if (bf16_mfma_eligible(p)) {
         // 128x128 tiles while all of them are resident at once (two workgroups per CU:
         // 512), 256x256 tiles beyond that (measured crossover on squares: 2816 -> 3072).
@@ -137,7 +137,10 @@ int choose_plan(const Problem &p, size_t workspace_bytes, int forced_variant, in
         if (t128 > 512) {
             plan.variant = V_BF16_PP256;
         } else {
-            plan.variant = V_BF16_128x128;
+            // Up to 256 tiles leave one workgroup per CU: the three-stage kernel hides the
+            // load latency there (2048^3: 24.8 against 27.8 us); between 257 and 512 tiles
+            // the two-stage kernel wins because two of its workgroups share a CU.
+            plan.variant = (t128 <= 256 && bf16_stream_eligible(p, 128)) ? V_BF16_STREAM128 : V_BF16_128x128;
             plan.split = split_for_small_grid(p, workspace_bytes);
         }
     }

@@ -46,7 +46,7 @@ bool bf16_pingpong_eligible(const Problem &p);
 hipError_t launch_bf16_pingpong(const Problem &p);
 
 // bf16_stream.hip
-bool bf16_stream_eligible(const Problem &p);
+bool bf16_stream_eligible(const Problem &p, int bm);
 hipError_t launch_bf16_stream(const Problem &p, int bm);
 
 }  // namespace brg
