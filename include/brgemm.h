@@ -125,6 +125,26 @@ int brgemm_fused(int in_dtype, int transA, int transB,
                  void *workspace, size_t workspace_bytes, void *stream);
 
 /*
+ * Batched matrix multiplication (Section 5(d): "batch matmul" next to batch-reduce
+ * matmul): nmat independent products of one shape in one call,
+ *     C_z = beta * C_z + A_z x B_z,     z = 0 .. nmat-1   (nmat <= 65535),
+ * where matrix z of an operand starts strideX ELEMENTS after matrix z-1.  strideA or
+ * strideB may be 0 (all products share that operand); strideC must be at least
+ * (M-1)*ldc + N so that the results do not overlap.  No reduction across z, no
+ * workspace.  All other arguments as in gemm_bf16 / gemm_f32; the alignment rules
+ * of the tuned kernels then also apply to the strides (multiples of 8 / 4 elements),
+ * otherwise the general kernel runs.
+ */
+int gemm_bf16_batched(int transA, int transB, int64_t M, int64_t N, int64_t K, int64_t nmat,
+                      const uint16_t *A, int64_t lda, int64_t strideA,
+                      const uint16_t *B, int64_t ldb, int64_t strideB,
+                      float beta, void *C, int64_t ldc, int64_t strideC, int c_is_f32, void *stream);
+int gemm_f32_batched(int transA, int transB, int64_t M, int64_t N, int64_t K, int64_t nmat,
+                     const float *A, int64_t lda, int64_t strideA,
+                     const float *B, int64_t ldb, int64_t strideB,
+                     float beta, float *C, int64_t ldc, int64_t strideC, void *stream);
+
+/*
  * Pre-packed B ("VNNI-packed layout", Section 2.2 and Figure 1; the comparison of
  * packed against flat operands is the axis of the paper's evaluation, Section 6).
  * Weights that are used many times can be re-laid-out once so that the kernels

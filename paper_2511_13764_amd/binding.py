@@ -29,7 +29,8 @@ EPI_NONE, EPI_BIAS, EPI_RELU = 0, 1, 2
 EXPORTS = ["gemm_f32", "gemm_bf16", "brgemm_bf16", "brgemm_fused", "gemm_workspace_bytes",
            "gemm_strerror", "gemm_last_hip_error", "gemm_force_variant", "gemm_variant_name",
            "gemm_last_variant", "gemm_last_split", "gemm_mfma_probe", "gemm_pack_vnni_bf16",
-           "gemm_packed_b_bytes", "gemm_pack_b_bf16", "gemm_bf16_packed"]
+           "gemm_packed_b_bytes", "gemm_pack_b_bf16", "gemm_bf16_packed", "gemm_bf16_batched",
+           "gemm_f32_batched"]
 
 _lib = None
 
@@ -82,6 +83,10 @@ def load():
     lib.gemm_pack_b_bf16.argtypes = [ci, i64, i64, vp, i64, vp, sz, vp]
     lib.gemm_bf16_packed.restype = ci
     lib.gemm_bf16_packed.argtypes = [ci, i64, i64, i64, vp, i64, vp, cf, vp, i64, ci, vp, ci, vp, sz, vp]
+    lib.gemm_bf16_batched.restype = ci
+    lib.gemm_bf16_batched.argtypes = [ci, ci, i64, i64, i64, i64, vp, i64, i64, vp, i64, i64, cf, vp, i64, i64, ci, vp]
+    lib.gemm_f32_batched.restype = ci
+    lib.gemm_f32_batched.argtypes = [ci, ci, i64, i64, i64, i64, vp, i64, i64, vp, i64, i64, cf, vp, i64, i64, vp]
     lib.gemm_mfma_probe.restype = ci
     lib.gemm_mfma_probe.argtypes = [ci, vp, i64, ci, vp, ctypes.POINTER(ctypes.c_double), vp]
     _lib = lib
@@ -171,6 +176,20 @@ def gemm_bf16_packed(transA, M, N, K, A, lda, packedB, beta, C, ldc, c_is_f32, b
     rc = load().gemm_bf16_packed(transA, M, N, K, _ptr(A), lda, _ptr(packedB), beta, _ptr(C), ldc,
                                  int(bool(c_is_f32)), _ptr(bias), epilogue, ws, nb, _stream(stream))
     return _check(rc, "gemm_bf16_packed", check)
+
+
+def gemm_bf16_batched(transA, transB, M, N, K, nmat, A, lda, strideA, B, ldb, strideB, beta, C, ldc, strideC,
+                      c_is_f32, stream=None, check=True):
+    rc = load().gemm_bf16_batched(transA, transB, M, N, K, nmat, _ptr(A), lda, strideA, _ptr(B), ldb, strideB,
+                                  beta, _ptr(C), ldc, strideC, int(bool(c_is_f32)), _stream(stream))
+    return _check(rc, "gemm_bf16_batched", check)
+
+
+def gemm_f32_batched(transA, transB, M, N, K, nmat, A, lda, strideA, B, ldb, strideB, beta, C, ldc, strideC,
+                     stream=None, check=True):
+    rc = load().gemm_f32_batched(transA, transB, M, N, K, nmat, _ptr(A), lda, strideA, _ptr(B), ldb, strideB,
+                                 beta, _ptr(C), ldc, strideC, _stream(stream))
+    return _check(rc, "gemm_f32_batched", check)
 
 
 def gemm_mfma_probe(dtype, operands, iters, blocks, sink, stream=None, check=True):

@@ -64,6 +64,8 @@ int finish(hipError_t e)
 
 int run(Problem &p, void *workspace, size_t workspace_bytes, bool need_offsets)
 {
+    if (p.nmat == 0)
+        p.nmat = 1;
     int rc = validate(p, workspace, workspace_bytes, need_offsets);
     if (rc != BRGEMM_OK)
         return rc;
@@ -231,6 +233,48 @@ int gemm_bf16_packed(int transA, int64_t M, int64_t N, int64_t K,
     p.relu = (epilogue & BRGEMM_EPI_RELU) ? 1 : 0;
     p.stream = (hipStream_t)stream;
     return run(p, workspace, workspace_bytes, false);
+}
+
+// Shared by the two batched entry points: the strides must describe matrices that fit
+// (a stride of 0 shares an input operand; C matrices must not overlap).
+static int run_batched(Problem &p, int64_t nmat, int64_t strideA, int64_t strideB, int64_t strideC)
+{
+    if (nmat < 0 || nmat > 65535 || strideA < 0 || strideB < 0 || strideC < 0)
+        return BRGEMM_INVALID_ARG;
+    if (nmat == 0)
+        return BRGEMM_OK;
+    if (nmat > 1 && p.M > 0 && p.N > 0 && strideC < (p.M - 1) * p.ldc + p.N)
+        return BRGEMM_INVALID_ARG;
+    p.nmat = nmat; p.ms_a = strideA; p.ms_b = strideB; p.ms_c = strideC;
+    return run(p, nullptr, 0, false);
+}
+
+int gemm_bf16_batched(int transA, int transB, int64_t M, int64_t N, int64_t K, int64_t nmat,
+                      const uint16_t *A, int64_t lda, int64_t strideA,
+                      const uint16_t *B, int64_t ldb, int64_t strideB,
+                      float beta, void *C, int64_t ldc, int64_t strideC, int c_is_f32, void *stream)
+{
+    Problem p{};
+    p.in_bf16 = 1; p.transA = transA; p.transB = transB;
+    p.M = M; p.N = N; p.K = K; p.batch = 1;
+    p.A = A; p.lda = lda; p.B = B; p.ldb = ldb;
+    p.beta = beta; p.C = C; p.ldc = ldc; p.c_f32 = c_is_f32 ? 1 : 0;
+    p.stream = (hipStream_t)stream;
+    return run_batched(p, nmat, strideA, strideB, strideC);
+}
+
+int gemm_f32_batched(int transA, int transB, int64_t M, int64_t N, int64_t K, int64_t nmat,
+                     const float *A, int64_t lda, int64_t strideA,
+                     const float *B, int64_t ldb, int64_t strideB,
+                     float beta, float *C, int64_t ldc, int64_t strideC, void *stream)
+{
+    Problem p{};
+    p.in_bf16 = 0; p.transA = transA; p.transB = transB;
+    p.M = M; p.N = N; p.K = K; p.batch = 1;
+    p.A = A; p.lda = lda; p.B = B; p.ldb = ldb;
+    p.beta = beta; p.C = C; p.ldc = ldc; p.c_f32 = 1;
+    p.stream = (hipStream_t)stream;
+    return run_batched(p, nmat, strideA, strideB, strideC);
 }
 
 size_t gemm_workspace_bytes(int dtype, int64_t M, int64_t N, int64_t K, int64_t batch)

@@ -40,6 +40,7 @@ bf16_mfma_kernel(Bf16Args p)
 
     extern __shared__ __attribute__((aligned(1024))) char smem_generic[];
     LDS_AS char *smem = (LDS_AS char *)smem_generic;
+    select_matrix(p);
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -215,15 +216,10 @@ template <int BM, int BN>
 static hipError_t launch_tile(const Problem &p)
 {
     Bf16Args a;
-    a.M = p.M; a.N = p.N; a.K = p.K; a.batch = p.batch;
-    a.A = (const uint16_t *)p.A; a.A_off = p.A_off; a.lda = p.lda;
-    a.B = (const uint16_t *)p.B; a.B_off = p.B_off; a.ldb = p.ldb;
-    a.epi.beta = p.beta; a.epi.C = p.C; a.epi.ldc = p.ldc; a.epi.c_f32 = p.c_f32;
-    a.epi.bias = p.bias; a.epi.relu = p.relu;
-    a.split = p.split; a.partial = p.partial;
+    fill_common_args(a, p);
     a.tiles_m = (int)((p.M + BM - 1) / BM);
     a.tiles_n = (int)((p.N + BN - 1) / BN);
-    const dim3 grid((unsigned)(a.tiles_m * a.tiles_n), (unsigned)p.split);
+    const dim3 grid((unsigned)(a.tiles_m * a.tiles_n), (unsigned)p.split, (unsigned)p.nmat);
     const size_t lds = 2 * (size_t)(BM + BN) * BK * 2;
     const bool ak = p.transA == 0;
     const int lay = p.b_packed ? LAY_PACKED : (p.transB == 1 ? LAY_K : LAY_MN);
@@ -259,6 +255,8 @@ bool bf16_mfma_eligible(const Problem &p)
     if (p.K % BK != 0)
         return false;
     if (((uintptr_t)p.A & 15) || ((uintptr_t)p.B & 15) || (p.lda & 7) || (p.ldb & 7))
+        return false;
+    if ((p.ms_a & 7) || (p.ms_b & 7))          // every matrix of a batched call starts 16-byte aligned
         return false;
     if (p.transA == 1 && (p.M & 7))
         return false;

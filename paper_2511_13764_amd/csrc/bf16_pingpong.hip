@@ -320,6 +320,7 @@ bf16_pingpong_kernel(Bf16Args p)
 {
     extern __shared__ __attribute__((aligned(1024))) char smem_generic[];
     LDS_AS char *smem = (LDS_AS char *)smem_generic;
+    select_matrix(p);
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -361,15 +362,10 @@ bf16_pingpong_kernel(Bf16Args p)
 static hipError_t launch_pp(const Problem &p)
 {
     Bf16Args a;
-    a.M = p.M; a.N = p.N; a.K = p.K; a.batch = p.batch;
-    a.A = (const uint16_t *)p.A; a.A_off = p.A_off; a.lda = p.lda;
-    a.B = (const uint16_t *)p.B; a.B_off = p.B_off; a.ldb = p.ldb;
-    a.epi.beta = p.beta; a.epi.C = p.C; a.epi.ldc = p.ldc; a.epi.c_f32 = p.c_f32;
-    a.epi.bias = p.bias; a.epi.relu = p.relu;
-    a.split = p.split; a.partial = p.partial;
+    fill_common_args(a, p);
     a.tiles_m = (int)((p.M + PP_BM - 1) / PP_BM);
     a.tiles_n = (int)((p.N + PP_BN - 1) / PP_BN);
-    const dim3 grid((unsigned)(a.tiles_m * a.tiles_n), (unsigned)p.split);
+    const dim3 grid((unsigned)(a.tiles_m * a.tiles_n), (unsigned)p.split, (unsigned)p.nmat);
     const size_t lds = (size_t)PP_SLOTS * PP_SLOT;
     const bool ak = p.transA == 0;
     const int lay = p.b_packed ? LAY_PACKED : (p.transB == 1 ? LAY_K : LAY_MN);

@@ -43,6 +43,7 @@ bf16_stream_kernel(Bf16Args p)
 
     extern __shared__ __attribute__((aligned(1024))) char smem_generic[];
     LDS_AS char *smem = (LDS_AS char *)smem_generic;
+    select_matrix(p);
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -140,15 +141,10 @@ template <int BM>
 hipError_t launch_stream(const Problem &p)
 {
     Bf16Args a;
-    a.M = p.M; a.N = p.N; a.K = p.K; a.batch = 1;
-    a.A = (const uint16_t *)p.A; a.A_off = nullptr; a.lda = p.lda;
-    a.B = (const uint16_t *)p.B; a.B_off = nullptr; a.ldb = p.ldb;
-    a.epi.beta = p.beta; a.epi.C = p.C; a.epi.ldc = p.ldc; a.epi.c_f32 = p.c_f32;
-    a.epi.bias = p.bias; a.epi.relu = p.relu;
-    a.split = p.split; a.partial = p.partial;
+    fill_common_args(a, p);
     a.tiles_m = (int)((p.M + BM - 1) / BM);
     a.tiles_n = (int)((p.N + ST_BN - 1) / ST_BN);
-    const dim3 grid((unsigned)(a.tiles_m * a.tiles_n), (unsigned)p.split);
+    const dim3 grid((unsigned)(a.tiles_m * a.tiles_n), (unsigned)p.split, (unsigned)p.nmat);
     const size_t lds = (size_t)ST_STAGES * (BM + ST_BN) * BK * 2;
     void (*kern)(Bf16Args) = p.b_packed ? bf16_stream_kernel<BM, true, LAY_PACKED>
                              : p.transB == 1 ? bf16_stream_kernel<BM, true, LAY_K> : bf16_stream_kernel<BM, true, LAY_MN>;

@@ -30,7 +30,29 @@ struct Bf16Args {
     int split;
     float *partial;
     int tiles_m, tiles_n;
+    int64_t ms_a, ms_b, ms_c;       // element strides between the matrices of a batched call (blockIdx.z)
 };
+
+// Batched matmul: point the arguments at matrix blockIdx.z.
+__device__ __forceinline__ void select_matrix(Bf16Args &p)
+{
+    const int64_t z = blockIdx.z;
+    p.A += z * p.ms_a;
+    p.B += z * p.ms_b;
+    p.epi.C = (char *)p.epi.C + z * p.ms_c * (p.epi.c_f32 ? 4 : 2);
+}
+
+// Host side: fill the fields every bf16 launcher shares.
+inline void fill_common_args(Bf16Args &a, const Problem &p)
+{
+    a.M = p.M; a.N = p.N; a.K = p.K; a.batch = p.batch;
+    a.A = (const uint16_t *)p.A; a.A_off = p.A_off; a.lda = p.lda;
+    a.B = (const uint16_t *)p.B; a.B_off = p.B_off; a.ldb = p.ldb;
+    a.epi.beta = p.beta; a.epi.C = p.C; a.epi.ldc = p.ldc; a.epi.c_f32 = p.c_f32;
+    a.epi.bias = p.bias; a.epi.relu = p.relu;
+    a.split = p.split; a.partial = p.partial;
+    a.ms_a = p.ms_a; a.ms_b = p.ms_b; a.ms_c = p.ms_c;
+}
 
 // s_waitcnt immediates for gfx9-family encodings: vmcnt in bits [3:0] and [15:14],
 // expcnt [6:4], lgkmcnt [11:8].

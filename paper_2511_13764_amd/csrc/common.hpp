@@ -35,6 +35,10 @@ struct Problem {
     // them in a fixed order and applies the epilogue (deterministic).
     int split;
     float *partial;
+    // Batched (non-reduce) matmul, Section 5(d): nmat independent problems of the same
+    // shape; matrix z uses A + z*ms_a, B + z*ms_b, C + z*ms_c (element strides, 0 = the
+    // operand is shared).  nmat > 1 excludes tile offsets and a split.
+    int64_t nmat, ms_a, ms_b, ms_c;
     hipStream_t stream;
 };
 

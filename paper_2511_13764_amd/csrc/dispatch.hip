@@ -125,15 +125,17 @@ static int split_for_f32(const Problem &p, size_t workspace_bytes)
 int choose_plan(const Problem &p, size_t workspace_bytes, int forced_variant, int forced_split, Plan *out)
 {
     Plan plan{V_GENERIC, 1};
+    // A batched call (nmat matrices) multiplies the tile count and never splits.
+    const bool single = p.nmat == 1;
     const int skinny_bm = p.M <= 32 ? 32 : p.M <= 64 ? 64 : 128;
     if (p.M <= 128 && bf16_stream_eligible(p, skinny_bm)) {
         // Few rows of A: the time goes into streaming B once.
         plan.variant = skinny_bm == 32 ? V_BF16_STREAM32 : skinny_bm == 64 ? V_BF16_STREAM64 : V_BF16_STREAM128;
-        plan.split = split_for_stream(p, skinny_bm, workspace_bytes);
+        plan.split = single ? split_for_stream(p, skinny_bm, workspace_bytes) : 1;
     } else if (bf16_mfma_eligible(p)) {
         // 128x128 tiles while all of them are resident at once (two workgroups per CU:
         // 512), 256x256 tiles beyond that (measured crossover on squares: 2816 -> 3072).
-        const int64_t t128 = ((p.M + 127) / 128) * ((p.N + 127) / 128);
+        const int64_t t128 = ((p.M + 127) / 128) * ((p.N + 127) / 128) * p.nmat;
         if (t128 > 512) {
             plan.variant = V_BF16_PP256;
         } else {
@@ -141,18 +143,20 @@ int choose_plan(const Problem &p, size_t workspace_bytes, int forced_variant, in
             // load latency there (2048^3: 24.8 against 27.8 us); between 257 and 512 tiles
             // the two-stage kernel wins because two of its workgroups share a CU.
             plan.variant = (t128 <= 256 && bf16_stream_eligible(p, 128)) ? V_BF16_STREAM128 : V_BF16_128x128;
-            plan.split = split_for_small_grid(p, workspace_bytes);
+            plan.split = single ? split_for_small_grid(p, workspace_bytes) : 1;
         }
     }
     if (f32_mfma_eligible(p)) {
         plan.variant = V_F32_128x128;
-        plan.split = split_for_f32(p, workspace_bytes);
+        plan.split = single ? split_for_f32(p, workspace_bytes) : 1;
     }
     if (forced_variant >= 0) {
         if (forced_variant >= V_COUNT || !variant_eligible(forced_variant, p))
             return BRGEMM_INVALID_ARG;
         plan.variant = forced_variant;
     }
+    if (forced_split > 1 && !single)
+        return BRGEMM_INVALID_ARG;
     if (forced_split > 0) {
         plan.split = forced_split;
         if (split_bytes(p, plan.split) > workspace_bytes)

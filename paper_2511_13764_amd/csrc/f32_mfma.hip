@@ -40,6 +40,7 @@ struct F32Args {
     int split;
     float *partial;
     int tiles_m, tiles_n;
+    int64_t ms_a, ms_b, ms_c;       // element strides between the matrices of a batched call
 };
 
 // k-contiguous operand: reuse the 128-byte-row image of the bf16 tiles (a float row
@@ -87,6 +88,9 @@ f32_mfma_kernel(F32Args p)
 
     extern __shared__ __attribute__((aligned(1024))) char smem_generic[];
     LDS_AS char *smem = (LDS_AS char *)smem_generic;
+    p.A += (int64_t)blockIdx.z * p.ms_a;
+    p.B += (int64_t)blockIdx.z * p.ms_b;
+    p.epi.C = (float *)p.epi.C + (int64_t)blockIdx.z * p.ms_c;
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -289,9 +293,10 @@ hipError_t launch_f32_128x128(const Problem &p)
     a.epi.beta = p.beta; a.epi.C = p.C; a.epi.ldc = p.ldc; a.epi.c_f32 = 1;
     a.epi.bias = p.bias; a.epi.relu = p.relu;
     a.split = p.split; a.partial = p.partial;
+    a.ms_a = p.ms_a; a.ms_b = p.ms_b; a.ms_c = p.ms_c;
     a.tiles_m = (int)((p.M + FB - 1) / FB);
     a.tiles_n = (int)((p.N + FB - 1) / FB);
-    const dim3 grid((unsigned)(a.tiles_m * a.tiles_n), (unsigned)p.split);
+    const dim3 grid((unsigned)(a.tiles_m * a.tiles_n), (unsigned)p.split, (unsigned)p.nmat);
     const size_t lds = 3 * (size_t)F_STAGE;
     const bool ak = p.transA == 0, bk = p.transB == 1;
     void (*kern)(F32Args) = nullptr;
@@ -325,6 +330,8 @@ bool f32_mfma_eligible(const Problem &p)
     if (p.K % FK != 0)
         return false;
     if (((uintptr_t)p.A & 15) || ((uintptr_t)p.B & 15) || (p.lda & 3) || (p.ldb & 3))
+        return false;
+    if ((p.ms_a & 3) || (p.ms_b & 3))
         return false;
     if (p.transA == 1 && (p.M & 3))
         return false;

@@ -163,14 +163,25 @@ static Epilogue make_epilogue(const Problem &p)
 hipError_t launch_generic(const Problem &p)
 {
     dim3 grid((unsigned)((p.N + GT - 1) / GT), (unsigned)((p.M + GT - 1) / GT), (unsigned)p.split);
-    Epilogue e = make_epilogue(p);
-    if (p.in_bf16)
-        hipLaunchKernelGGL(generic_kernel<true>, grid, dim3(256), 0, p.stream, p.transA, p.b_packed ? 2 : p.transB, p.M, p.N,
-                           p.K, p.batch, p.A, p.A_off, p.lda, p.B, p.B_off, p.ldb, e, p.split, p.partial);
-    else
-        hipLaunchKernelGGL(generic_kernel<false>, grid, dim3(256), 0, p.stream, p.transA, p.transB, p.M, p.N,
-                           p.K, p.batch, p.A, p.A_off, p.lda, p.B, p.B_off, p.ldb, e, p.split, p.partial);
-    return hipGetLastError();
+    // A batched call runs one launch per matrix here (this is the slow general path).
+    const int64_t esz = p.in_bf16 ? 2 : 4, csz = p.c_f32 ? 4 : 2;
+    for (int64_t z = 0; z < p.nmat; ++z) {
+        Epilogue e = make_epilogue(p);
+        e.C = (char *)p.C + z * p.ms_c * csz;
+        const void *A = (const char *)p.A + z * p.ms_a * esz;
+        const void *B = (const char *)p.B + z * p.ms_b * esz;
+        if (p.in_bf16)
+            hipLaunchKernelGGL(generic_kernel<true>, grid, dim3(256), 0, p.stream, p.transA,
+                               p.b_packed ? 2 : p.transB, p.M, p.N, p.K, p.batch, A, p.A_off, p.lda, B, p.B_off,
+                               p.ldb, e, p.split, p.partial);
+        else
+            hipLaunchKernelGGL(generic_kernel<false>, grid, dim3(256), 0, p.stream, p.transA, p.transB, p.M, p.N,
+                               p.K, p.batch, A, p.A_off, p.lda, B, p.B_off, p.ldb, e, p.split, p.partial);
+        hipError_t err = hipGetLastError();
+        if (err != hipSuccess)
+            return err;
+    }
+    return hipSuccess;
 }
 
 static unsigned elementwise_grid(int64_t total)
@@ -198,9 +209,15 @@ hipError_t launch_reduce(const Problem &p)
 
 hipError_t launch_scale_only(const Problem &p)
 {
-    hipLaunchKernelGGL(scale_only_kernel, dim3(elementwise_grid(p.M * p.N)), dim3(256), 0, p.stream, p.M, p.N,
-                       make_epilogue(p));
-    return hipGetLastError();
+    for (int64_t z = 0; z < p.nmat; ++z) {
+        Epilogue e = make_epilogue(p);
+        e.C = (char *)p.C + z * p.ms_c * (p.c_f32 ? 4 : 2);
+        hipLaunchKernelGGL(scale_only_kernel, dim3(elementwise_grid(p.M * p.N)), dim3(256), 0, p.stream, p.M, p.N, e);
+        hipError_t err = hipGetLastError();
+        if (err != hipSuccess)
+            return err;
+    }
+    return hipSuccess;
 }
 
 }  // namespace brg

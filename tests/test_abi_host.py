@@ -151,3 +151,20 @@ def test_packed_b_size_and_argument_rules(lib):
     assert B.gemm_bf16_packed(0, 4, 8, 16, P, 16, P, 0.0, P, 8, 0, epilogue=B.EPI_BIAS, stream=0,
                               check=False) == B.INVALID_ARG
     assert B.gemm_bf16_packed(0, 4, 8, 16, P, 15, P, 0.0, P, 8, 0, stream=0, check=False) == B.INVALID_ARG
+
+
+def test_batched_argument_rules(lib):
+    def call(**kw):
+        a = dict(tA=0, tB=0, M=4, N=8, K=16, nmat=3, A=P, lda=16, sA=64, B=P, ldb=8, sB=128, beta=0.0, C=P, ldc=8,
+                 sC=32, f32=0)
+        a.update(kw)
+        return B.gemm_bf16_batched(a["tA"], a["tB"], a["M"], a["N"], a["K"], a["nmat"], a["A"], a["lda"], a["sA"],
+                                   a["B"], a["ldb"], a["sB"], a["beta"], a["C"], a["ldc"], a["sC"], a["f32"],
+                                   stream=0, check=False)
+    assert call(nmat=0) == B.OK                       # nothing to do
+    assert call(M=0) == B.OK
+    for kw in (dict(nmat=-1), dict(nmat=65536), dict(sA=-1), dict(sB=-8), dict(sC=31), dict(lda=15), dict(A=0),
+               dict(tA=3)):
+        assert call(**kw) == B.INVALID_ARG, kw
+    assert B.gemm_f32_batched(0, 0, 4, 8, 16, 2, P, 16, 64, P, 8, 128, 0.0, P, 8, 3, stream=0, check=False) == \
+        B.INVALID_ARG                                  # C matrices would overlap
