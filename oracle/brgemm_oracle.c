@@ -37,8 +37,8 @@
  * integers/fractions, small-integer matrices against int64 arithmetic,
  * identity/permutation matrices, closed forms, associativity, transpose
  * identity, BRGEMM == GEMM on K-concatenated operands, beta linearity, the
- * paper's listing shapes, and the bf16 rounding helper against hand-picked bit
- * patterns and a library conversion.
+ * paper's listing shapes, the bf16 and binary16 helpers against hand-picked bit
+ * patterns and a library conversion, and the VNNI packer against Figure 1.
  */
 #include <math.h>
 #include <stdint.h>
@@ -48,7 +48,7 @@
 #include <omp.h>
 #endif
 
-enum { ORACLE_F32 = 0, ORACLE_BF16 = 1 };
+enum { ORACLE_F32 = 0, ORACLE_BF16 = 1, ORACLE_F16 = 2 };
 
 /* bf16 is the upper half of an IEEE-754 binary32; widening is exact. */
 static double widen_bf16(uint16_t h)
@@ -59,10 +59,27 @@ static double widen_bf16(uint16_t h)
     return (double)f;
 }
 
+/* IEEE-754 binary16 (1 sign, 5 exponent bits with bias 15, 10 fraction bits), the
+ * other 16-bit type Section 2.2 names; widening is exact.  Done on values. */
+static double widen_f16(uint16_t h)
+{
+    const int sign = h >> 15, e = (h >> 10) & 31, f = h & 1023;
+    double v;
+    if (e == 31)
+        v = f ? NAN : INFINITY;
+    else if (e == 0)
+        v = ldexp((double)f, -24);                  /* subnormal: f * 2^-24 */
+    else
+        v = ldexp(1.0 + (double)f / 1024.0, e - 15);
+    return sign ? -v : v;
+}
+
 static double load_elem(const void *p, int dtype, int64_t idx)
 {
     if (dtype == ORACLE_BF16)
         return widen_bf16(((const uint16_t *)p)[idx]);
+    if (dtype == ORACLE_F16)
+        return widen_f16(((const uint16_t *)p)[idx]);
     return (double)((const float *)p)[idx];
 }
 
@@ -102,14 +119,56 @@ uint16_t oracle_f64_to_bf16(double d)
 
 double oracle_bf16_to_f64(uint16_t h) { return widen_bf16(h); }
 
+/*
+ * Round an fp64 value to binary16 with round-to-nearest, ties-to-even, in one
+ * step, the same way as above: one quantum of the target is scaled to 1.0, rint()
+ * rounds, and the rounded value is encoded.  Subnormals (quantum 2^-24) are kept;
+ * values that round beyond 65504 become infinity; NaN becomes a quiet NaN.
+ */
+uint16_t oracle_f64_to_f16(double d)
+{
+    uint16_t sign = signbit(d) ? 0x8000u : 0u;
+    if (isnan(d))
+        return (uint16_t)(sign | 0x7E00u);
+    double a = fabs(d);
+    if (a == 0.0)
+        return sign;
+    /* halfway between 65504 = (2 - 2^-10) * 2^15 and 2^16: ties go to the even
+     * neighbour, which is 2^16, i.e. infinity */
+    const double to_inf = ldexp(2.0 - ldexp(1.0, -11), 15);
+    if (isinf(d) || a >= to_inf)
+        return (uint16_t)(sign | 0x7C00u);
+    int e2;
+    (void)frexp(a, &e2);
+    int E = e2 - 1;                     /* a in [2^E, 2^(E+1)) */
+    if (E < -14)
+        E = -14;                        /* subnormal range: fixed quantum 2^-24 */
+    const int qexp = E - 10;
+    const double r = rint(ldexp(a, -qexp));      /* integer number of quanta */
+    const double v = ldexp(r, qexp);
+    if (v == 0.0)
+        return sign;
+    (void)frexp(v, &e2);
+    const int Ev = e2 - 1;              /* may be E + 1 after a carry */
+    if (Ev < -14)                       /* subnormal result */
+        return (uint16_t)(sign | (uint16_t)ldexp(v, 24));
+    const double frac = ldexp(v, -Ev) - 1.0;     /* in [0, 1) */
+    return (uint16_t)(sign | (uint16_t)((Ev + 15) << 10) | (uint16_t)ldexp(frac, 10));
+}
+
+double oracle_f16_to_f64(uint16_t h) { return widen_f16(h); }
+
 /* Element-wise rounding of an fp64 array to the output type of the GPU
- * library: out_dtype 0 -> fp32 (C cast, round-to-nearest-even), 1 -> bf16. */
+ * library: out_dtype 0 -> fp32 (C cast, round-to-nearest-even), 1 -> bf16,
+ * 2 -> binary16. */
 void oracle_round_to_out(const double *ref, int64_t count, int out_dtype,
                          void *out)
 {
     for (int64_t t = 0; t < count; ++t) {
         if (out_dtype == ORACLE_BF16)
             ((uint16_t *)out)[t] = oracle_f64_to_bf16(ref[t]);
+        else if (out_dtype == ORACLE_F16)
+            ((uint16_t *)out)[t] = oracle_f64_to_f16(ref[t]);
         else
             ((float *)out)[t] = (float)ref[t];
     }
@@ -127,7 +186,7 @@ int oracle_num_threads(void)
 /*
  * The oracle proper.
  *
- *   in_dtype    element type of every A_i and B_i (ORACLE_F32 / ORACLE_BF16)
+ *   in_dtype    element type of every A_i and B_i (ORACLE_F32 / ORACLE_BF16 / ORACLE_F16)
  *   transA      0: A_i stored M x K, element (m,k) at m*lda + k
  *               1: A_i stored K x M, element (m,k) at k*lda + m
  *   transB      0: B_i stored K x N, element (k,n) at k*ldb + n

@@ -21,7 +21,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB_PATH = os.path.join(_HERE, "liboracle_brgemm.so")
 _lib = None
 
-F32, BF16 = 0, 1
+F32, BF16, F16 = 0, 1, 2
 
 
 def _load():
@@ -44,6 +44,10 @@ def _load():
     lib.oracle_f64_to_bf16.argtypes = [ctypes.c_double]
     lib.oracle_bf16_to_f64.restype = ctypes.c_double
     lib.oracle_bf16_to_f64.argtypes = [ctypes.c_uint16]
+    lib.oracle_f64_to_f16.restype = ctypes.c_uint16
+    lib.oracle_f64_to_f16.argtypes = [ctypes.c_double]
+    lib.oracle_f16_to_f64.restype = ctypes.c_double
+    lib.oracle_f16_to_f64.argtypes = [ctypes.c_uint16]
     lib.oracle_num_threads.restype = cint
     lib.oracle_num_threads.argtypes = []
     lib.oracle_pack_vnni.restype = cint
@@ -57,7 +61,9 @@ def _dtype_code(a):
         return F32
     if a.dtype == np.uint16:
         return BF16
-    raise TypeError(f"oracle takes float32 or uint16 (bf16 bits), got {a.dtype}")
+    if a.dtype == np.float16:
+        return F16
+    raise TypeError(f"oracle takes float32, uint16 (bf16 bits) or float16, got {a.dtype}")
 
 
 def _ptr(a):
@@ -138,13 +144,23 @@ def round_to_out(ref, out_dtype):
     """Round an fp64 result once to the library's output type (F32 or BF16 bits)."""
     lib = _load()
     ref = np.ascontiguousarray(ref, dtype=np.float64)
-    out = np.empty(ref.shape, dtype=np.uint16 if out_dtype == BF16 else np.float32)
+    out = np.empty(ref.shape, dtype={BF16: np.uint16, F16: np.float16}.get(out_dtype, np.float32))
     lib.oracle_round_to_out(_ptr(ref), ref.size, out_dtype, _ptr(out))
     return out
 
 
 def f64_to_bf16(x):
     return int(_load().oracle_f64_to_bf16(float(x)))
+
+
+def f64_to_f16(x):
+    """fp64 -> binary16 bit pattern, round-to-nearest-even (the oracle's own rounding)."""
+    return int(_load().oracle_f64_to_f16(float(x)))
+
+
+def f16_to_f64(bits):
+    """Exact widening of one binary16 bit pattern to fp64 (the oracle's own decoder)."""
+    return float(_load().oracle_f16_to_f64(int(bits)))
 
 
 def bf16_to_f64(bits):

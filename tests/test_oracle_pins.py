@@ -463,3 +463,67 @@ def test_packed_gemm_identity(oracle):
     ref = oracle.gemm_ref(bf16_bits(A), K, bf16_bits(Bm), N, M, N, K)
     assert (ref == want).all()
     assert (ref == (A.astype(np.int64) @ Bm.astype(np.int64))).all()
+
+
+# ---------------------------------------------------------------- binary16 (Section 2.2 names FP16 next to BF16)
+
+def test_f16_decoder_all_patterns_against_library(oracle):
+    """Every one of the 65536 binary16 patterns decodes to what numpy's float16 says."""
+    bits = np.arange(65536, dtype=np.uint16)
+    lib = bits.view(np.float16).astype(np.float64)
+    for b in list(range(0, 65536, 7)) + [0, 1, 0x03FF, 0x0400, 0x7BFF, 0x7C00, 0x8000, 0x8001, 0xFBFF, 0xFC00]:
+        got = oracle.f16_to_f64(b)
+        assert (np.isnan(got) and np.isnan(lib[b])) or got == lib[b], hex(b)
+    # hand-picked values: smallest subnormal, largest subnormal, smallest normal, one, largest finite
+    assert oracle.f16_to_f64(0x0001) == 2.0 ** -24
+    assert oracle.f16_to_f64(0x03FF) == 1023 * 2.0 ** -24
+    assert oracle.f16_to_f64(0x0400) == 2.0 ** -14
+    assert oracle.f16_to_f64(0x3C00) == 1.0
+    assert oracle.f16_to_f64(0x7BFF) == 65504.0
+    assert oracle.f16_to_f64(0xC000) == -2.0
+
+
+def test_f16_rounding_hand_picked_and_against_library(oracle):
+    f = oracle.f64_to_f16
+    assert f(0.0) == 0x0000 and f(-0.0) == 0x8000
+    assert f(1.0) == 0x3C00
+    assert f(1.0 + 2.0 ** -11) == 0x3C00            # tie: 1 is even
+    assert f(1.0 + 3 * 2.0 ** -11) == 0x3C02        # tie: goes to the even neighbour above
+    assert f(1.0 + 2.0 ** -11 + 2.0 ** -30) == 0x3C01
+    assert f(2.0 - 2.0 ** -12) == 0x4000            # carry into the exponent
+    assert f(65504.0) == 0x7BFF and f(65519.99) == 0x7BFF
+    assert f(65520.0) == 0x7C00 and f(1e9) == 0x7C00 and f(-1e9) == 0xFC00
+    assert f(2.0 ** -24) == 0x0001 and f(2.0 ** -25) == 0x0000      # tie to even (zero)
+    assert f(3 * 2.0 ** -25) == 0x0002 and f(2.0 ** -14 - 2.0 ** -25) == 0x0400
+    assert f(float("inf")) == 0x7C00 and (f(float("nan")) & 0x7FFF) > 0x7C00
+    rng = np.random.default_rng(11)
+    x = np.concatenate([rng.standard_normal(200000) * 10.0 ** rng.integers(-9, 5, 200000),
+                        (rng.integers(0, 65536, 50000).astype(np.uint16).view(np.float16).astype(np.float64)
+                         * (1 + rng.integers(-1, 2, 50000) * 2.0 ** -11))])
+    with np.errstate(over="ignore", invalid="ignore"):
+        lib = x.astype(np.float16).view(np.uint16)
+    got = oracle.round_to_out(x, 2).view(np.uint16)
+    nan = np.isnan(x)
+    assert (got[~nan] == lib[~nan]).all()
+
+
+def test_f16_gemm_small_integers_and_statistics(oracle):
+    """binary16 operands: integer-valued matrices are exact against int64 arithmetic in every
+    transpose; N(0,1) operands agree with a float64 library product of the widened inputs."""
+    M, N, K = 17, 23, 40
+    A = W.small_int_matrix(60, (M, K)).astype(np.float16)
+    Bm = W.small_int_matrix(61, (K, N)).astype(np.float16)
+    want = A.astype(np.int64) @ Bm.astype(np.int64)
+    for tA in (0, 1):
+        for tB in (0, 1):
+            As = np.ascontiguousarray(A.T if tA else A)
+            Bs = np.ascontiguousarray(Bm.T if tB else Bm)
+            ref = oracle.gemm_ref(As, As.shape[1], Bs, Bs.shape[1], M, N, K, transA=tA, transB=tB)
+            assert (ref == want).all(), (tA, tB)
+    rng = np.random.default_rng(12)
+    A = rng.standard_normal((64, 300)).astype(np.float16)
+    Bm = rng.standard_normal((300, 48)).astype(np.float16)
+    C0 = rng.standard_normal((64, 48)).astype(np.float16)
+    ref = oracle.gemm_ref(A, 300, Bm, 48, 64, 48, 300, beta=0.5, C0=C0, ldc0=48)
+    lib = 0.5 * C0.astype(np.float64) + A.astype(np.float64) @ Bm.astype(np.float64)
+    assert np.abs(ref - lib).max() <= 1e-12 * np.abs(lib).max()
