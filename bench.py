@@ -208,6 +208,14 @@ def main():
                    lambda: B.gemm_bf16(0, 0, s, s, s, a, s, b, s, 0.0, c, s, 0, workspace=ws), PEAK_BF16,
                    steps=20 if s == 8192 else 100)
             del a, b, c
+        # binary16 operands and results, same kernels with the f16 matrix instruction
+        a = torch.randn((4096, 4096), device="cuda").to(torch.float16)
+        b = torch.randn((4096, 4096), device="cuda").to(torch.float16)
+        c = torch.empty((4096, 4096), device="cuda", dtype=torch.float16)
+        record("f16_4096", 2.0 * 4096 ** 3,
+               lambda: B.gemm_f16(0, 0, 4096, 4096, 4096, a, 4096, b, 4096, 0.0, c, 4096, 0, workspace=ws), PEAK_BF16,
+               steps=100)
+        del a, b, c
         # MLP shapes, weights stored N x K
         # The skinny cases are bound by the stream of the 90 MB weight matrix, which fits
         # the 256 MB last-level cache: "warm" repeats one matrix, "cold" rotates over four

@@ -68,7 +68,7 @@ enum {
 };
 
 /* Element types, for gemm_workspace_bytes(). */
-enum { BRGEMM_DTYPE_F32 = 0, BRGEMM_DTYPE_BF16 = 1 };
+enum { BRGEMM_DTYPE_F32 = 0, BRGEMM_DTYPE_BF16 = 1, BRGEMM_DTYPE_F16 = 2 };
 
 /* Epilogue flags (Section 6: the measured "MLP kernel" fuses bias and ReLU
  * before the store of the accumulator). */
@@ -95,6 +95,18 @@ int gemm_bf16(int transA, int transB, int64_t M, int64_t N, int64_t K,
               void *workspace, size_t workspace_bytes, void *stream);
 
 /*
+ * The same for IEEE binary16 operands (Section 2.2 names FP16 beside BF16 among
+ * the mixed-precision types; Section 5(c): other packed types follow the same
+ * structure).  A, B: device, binary16 bit patterns; products and sums are fp32;
+ * C is fp32 if c_is_f32 != 0, else binary16 (widened on read, rounded to
+ * nearest-even once on store, subnormals kept, overflow to infinity).
+ */
+int gemm_f16(int transA, int transB, int64_t M, int64_t N, int64_t K,
+             const uint16_t *A, int64_t lda, const uint16_t *B, int64_t ldb,
+             float beta, void *C, int64_t ldc, int c_is_f32,
+             void *workspace, size_t workspace_bytes, void *stream);
+
+/*
  * bf16 batch-reduce GEMM into an fp32 C (Algorithm 1 as a whole; Section 2.1:
  * the source tiles need not be contiguous).  Tile i of A starts at element
  * A_base + A_off[i], tile i of B at B_base + B_off[i]; M, N, K, lda, ldb and
@@ -113,8 +125,9 @@ int brgemm_bf16(int transA, int transB, int64_t M, int64_t N, int64_t K, int64_t
  *     C = act( beta*C + sum_i A_i x B_i + bias[n] )
  * `epilogue` is a bit set of BRGEMM_EPI_BIAS (bias: device, N fp32 values, may
  * be NULL when the flag is clear) and BRGEMM_EPI_RELU (negative results become
- * +0; NaN stays NaN).  in_dtype selects fp32 or bf16 operands; for fp32
- * operands C is fp32.  batch == 1 with NULL offset arrays is plain GEMM.
+ * +0; NaN stays NaN).  in_dtype selects fp32, bf16 or binary16 operands; for fp32
+ * operands C is fp32, for 16-bit operands C is fp32 or the operands' own type.
+ * batch == 1 with NULL offset arrays is plain GEMM.
  */
 int brgemm_fused(int in_dtype, int transA, int transB,
                  int64_t M, int64_t N, int64_t K, int64_t batch,

@@ -23,14 +23,14 @@ UNSUPPORTED = -2
 WORKSPACE_TOO_SMALL = -3
 HIP_ERROR = -4
 MISALIGNED_WORKSPACE = -5
-DTYPE_F32, DTYPE_BF16 = 0, 1
+DTYPE_F32, DTYPE_BF16, DTYPE_F16 = 0, 1, 2
 EPI_NONE, EPI_BIAS, EPI_RELU = 0, 1, 2
 
 EXPORTS = ["gemm_f32", "gemm_bf16", "brgemm_bf16", "brgemm_fused", "gemm_workspace_bytes",
            "gemm_strerror", "gemm_last_hip_error", "gemm_force_variant", "gemm_variant_name",
            "gemm_last_variant", "gemm_last_split", "gemm_mfma_probe", "gemm_pack_vnni_bf16",
            "gemm_packed_b_bytes", "gemm_pack_b_bf16", "gemm_bf16_packed", "gemm_bf16_batched",
-           "gemm_f32_batched"]
+           "gemm_f32_batched", "gemm_f16"]
 
 _lib = None
 
@@ -56,6 +56,8 @@ def load():
     lib.gemm_f32.argtypes = [ci, ci, i64, i64, i64, vp, i64, vp, i64, cf, vp, i64, vp, sz, vp]
     lib.gemm_bf16.restype = ci
     lib.gemm_bf16.argtypes = [ci, ci, i64, i64, i64, vp, i64, vp, i64, cf, vp, i64, ci, vp, sz, vp]
+    lib.gemm_f16.restype = ci
+    lib.gemm_f16.argtypes = [ci, ci, i64, i64, i64, vp, i64, vp, i64, cf, vp, i64, ci, vp, sz, vp]
     lib.brgemm_bf16.restype = ci
     lib.brgemm_bf16.argtypes = [ci, ci, i64, i64, i64, i64, vp, vp, i64, vp, vp, i64, cf, vp, i64, vp, sz, vp]
     lib.brgemm_fused.restype = ci
@@ -135,6 +137,14 @@ def gemm_bf16(transA, transB, M, N, K, A, lda, B, ldb, beta, C, ldc, c_is_f32, w
     rc = load().gemm_bf16(transA, transB, M, N, K, _ptr(A), lda, _ptr(B), ldb, beta, _ptr(C), ldc,
                           int(bool(c_is_f32)), ws, nb, _stream(stream))
     return _check(rc, "gemm_bf16", check)
+
+
+def gemm_f16(transA, transB, M, N, K, A, lda, B, ldb, beta, C, ldc, c_is_f32, workspace=None, stream=None,
+             check=True):
+    ws, nb = _ws(workspace)
+    rc = load().gemm_f16(transA, transB, M, N, K, _ptr(A), lda, _ptr(B), ldb, beta, _ptr(C), ldc,
+                         int(bool(c_is_f32)), ws, nb, _stream(stream))
+    return _check(rc, "gemm_f16", check)
 
 
 def brgemm_bf16(transA, transB, M, N, K, batch, A_base, A_off, lda, B_base, B_off, ldb, beta, C, ldc,

@@ -128,6 +128,20 @@ int gemm_bf16(int transA, int transB, int64_t M, int64_t N, int64_t K,
     return run(p, workspace, workspace_bytes, false);
 }
 
+int gemm_f16(int transA, int transB, int64_t M, int64_t N, int64_t K,
+             const uint16_t *A, int64_t lda, const uint16_t *B, int64_t ldb,
+             float beta, void *C, int64_t ldc, int c_is_f32,
+             void *workspace, size_t workspace_bytes, void *stream)
+{
+    Problem p{};
+    p.in_f16 = 1; p.transA = transA; p.transB = transB;
+    p.M = M; p.N = N; p.K = K; p.batch = 1;
+    p.A = A; p.lda = lda; p.B = B; p.ldb = ldb;
+    p.beta = beta; p.C = C; p.ldc = ldc; p.c_f32 = c_is_f32 ? 1 : 0;
+    p.stream = (hipStream_t)stream;
+    return run(p, workspace, workspace_bytes, false);
+}
+
 int brgemm_bf16(int transA, int transB, int64_t M, int64_t N, int64_t K, int64_t batch,
                 const uint16_t *A_base, const int64_t *A_off, int64_t lda,
                 const uint16_t *B_base, const int64_t *B_off, int64_t ldb,
@@ -152,7 +166,7 @@ int brgemm_fused(int in_dtype, int transA, int transB,
                  const float *bias, int epilogue,
                  void *workspace, size_t workspace_bytes, void *stream)
 {
-    if (in_dtype != BRGEMM_DTYPE_F32 && in_dtype != BRGEMM_DTYPE_BF16)
+    if (in_dtype != BRGEMM_DTYPE_F32 && in_dtype != BRGEMM_DTYPE_BF16 && in_dtype != BRGEMM_DTYPE_F16)
         return BRGEMM_INVALID_ARG;
     if (epilogue & ~(BRGEMM_EPI_BIAS | BRGEMM_EPI_RELU))
         return BRGEMM_INVALID_ARG;
@@ -161,7 +175,8 @@ int brgemm_fused(int in_dtype, int transA, int transB,
     if (in_dtype == BRGEMM_DTYPE_F32 && !c_is_f32)
         return BRGEMM_INVALID_ARG;
     Problem p{};
-    p.in_bf16 = in_dtype == BRGEMM_DTYPE_BF16; p.transA = transA; p.transB = transB;
+    p.in_bf16 = in_dtype == BRGEMM_DTYPE_BF16; p.in_f16 = in_dtype == BRGEMM_DTYPE_F16;
+    p.transA = transA; p.transB = transB;
     p.M = M; p.N = N; p.K = K; p.batch = batch;
     p.A = A_base; p.A_off = A_off; p.lda = lda;
     p.B = B_base; p.B_off = B_off; p.ldb = ldb;

@@ -27,7 +27,7 @@
 
 namespace brg {
 
-template <int BM, int BN, bool A_KMAJ, int B_LAY>
+template <int BM, int BN, bool A_KMAJ, int B_LAY, bool F16>
 __global__ void __launch_bounds__(256)
 bf16_mfma_kernel(Bf16Args p)
 {
@@ -157,7 +157,7 @@ bf16_mfma_kernel(Bf16Args p)
         for (int a = 0; a < TN; ++a)
 #pragma unroll
             for (int b = 0; b < TM; ++b)
-                acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[buf][a], fa[buf][b], acc[a][b], 0, 0, 0);
+                acc[a][b] = mfma_32x32x16<F16>(fb[buf][a], fa[buf][b], acc[a][b]);
     };
 
     if (n_iter > 0) {
@@ -224,13 +224,16 @@ static hipError_t launch_tile(const Problem &p)
     const bool ak = p.transA == 0;
     const int lay = p.b_packed ? LAY_PACKED : (p.transB == 1 ? LAY_K : LAY_MN);
     void (*kern)(Bf16Args) = nullptr;
-    if (ak && lay == LAY_K) kern = bf16_mfma_kernel<BM, BN, true, LAY_K>;
-    else if (ak && lay == LAY_MN) kern = bf16_mfma_kernel<BM, BN, true, LAY_MN>;
-    else if (ak) kern = bf16_mfma_kernel<BM, BN, true, LAY_PACKED>;
-    else if (lay == LAY_K) kern = bf16_mfma_kernel<BM, BN, false, LAY_K>;
-    else if (lay == LAY_MN) kern = bf16_mfma_kernel<BM, BN, false, LAY_MN>;
-    else kern = bf16_mfma_kernel<BM, BN, false, LAY_PACKED>;
-    static thread_local const void *configured[12] = {nullptr};
+#define BRG_PICK(F16)                                                                        \
+    if (ak && lay == LAY_K) kern = bf16_mfma_kernel<BM, BN, true, LAY_K, F16>;                \
+    else if (ak && lay == LAY_MN) kern = bf16_mfma_kernel<BM, BN, true, LAY_MN, F16>;         \
+    else if (ak) kern = bf16_mfma_kernel<BM, BN, true, LAY_PACKED, F16>;                      \
+    else if (lay == LAY_K) kern = bf16_mfma_kernel<BM, BN, false, LAY_K, F16>;                \
+    else if (lay == LAY_MN) kern = bf16_mfma_kernel<BM, BN, false, LAY_MN, F16>;              \
+    else kern = bf16_mfma_kernel<BM, BN, false, LAY_PACKED, F16>;
+    if (p.in_f16) { BRG_PICK(true) } else { BRG_PICK(false) }
+#undef BRG_PICK
+    static thread_local const void *configured[24] = {nullptr};
     bool done = false;
     for (const void *c : configured)
         done = done || c == (const void *)kern;
@@ -250,7 +253,7 @@ hipError_t launch_bf16_128x128(const Problem &p) { return launch_tile<128, 128>(
 // Alignment and shape rules of the kernels in this file.
 bool bf16_mfma_eligible(const Problem &p)
 {
-    if (!p.in_bf16)
+    if (!in_16bit(p))
         return false;
     if (p.K % BK != 0)
         return false;

@@ -13,6 +13,27 @@ typedef __attribute__((ext_vector_type(4))) float f32x4;
 typedef __attribute__((ext_vector_type(4))) short s16x4;
 typedef __attribute__((ext_vector_type(8))) short s16x8;
 
+typedef __attribute__((ext_vector_type(8))) _Float16 f16x8;
+
+// The matrix instruction for either 16-bit operand type (fragments travel as bf16x8
+// registers; only the instruction differs).
+template <bool F16>
+__device__ __forceinline__ f32x4 mfma_16x16x32(bf16x8 a, bf16x8 b, f32x4 c)
+{
+    if constexpr (F16)
+        return __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(f16x8, a), __builtin_bit_cast(f16x8, b), c, 0, 0, 0);
+    else
+        return __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, c, 0, 0, 0);
+}
+template <bool F16>
+__device__ __forceinline__ f32x16 mfma_32x32x16(bf16x8 a, bf16x8 b, f32x16 c)
+{
+    if constexpr (F16)
+        return __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(f16x8, a), __builtin_bit_cast(f16x8, b), c, 0, 0, 0);
+    else
+        return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
+}
+
 #define LDS_AS __attribute__((address_space(3)))
 #define GLB_AS __attribute__((address_space(1)))
 
@@ -48,7 +69,7 @@ inline void fill_common_args(Bf16Args &a, const Problem &p)
     a.M = p.M; a.N = p.N; a.K = p.K; a.batch = p.batch;
     a.A = (const uint16_t *)p.A; a.A_off = p.A_off; a.lda = p.lda;
     a.B = (const uint16_t *)p.B; a.B_off = p.B_off; a.ldb = p.ldb;
-    a.epi.beta = p.beta; a.epi.C = p.C; a.epi.ldc = p.ldc; a.epi.c_f32 = p.c_f32;
+    a.epi.beta = p.beta; a.epi.C = p.C; a.epi.ldc = p.ldc; a.epi.c_f32 = p.c_f32; a.epi.c_f16 = p.in_f16;
     a.epi.bias = p.bias; a.epi.relu = p.relu;
     a.split = p.split; a.partial = p.partial;
     a.ms_a = p.ms_a; a.ms_b = p.ms_b; a.ms_c = p.ms_c;
@@ -426,10 +447,10 @@ __device__ __forceinline__ void store4_epilogue(const Epilogue &e, int64_t m, in
             v3 = fmaf(e.beta, old[3], v3);
         } else {
             const uint2 old = *(const uint2 *)((const uint16_t *)e.C + m * e.ldc + n);
-            v0 = fmaf(e.beta, __uint_as_float(old.x << 16), v0);
-            v1 = fmaf(e.beta, __uint_as_float(old.x & 0xffff0000u), v1);
-            v2 = fmaf(e.beta, __uint_as_float(old.y << 16), v2);
-            v3 = fmaf(e.beta, __uint_as_float(old.y & 0xffff0000u), v3);
+            v0 = fmaf(e.beta, c16_to_f32((uint16_t)old.x, e.c_f16), v0);
+            v1 = fmaf(e.beta, c16_to_f32((uint16_t)(old.x >> 16), e.c_f16), v1);
+            v2 = fmaf(e.beta, c16_to_f32((uint16_t)old.y, e.c_f16), v2);
+            v3 = fmaf(e.beta, c16_to_f32((uint16_t)(old.y >> 16), e.c_f16), v3);
         }
     }
     if (e.bias) {
@@ -446,8 +467,8 @@ __device__ __forceinline__ void store4_epilogue(const Epilogue &e, int64_t m, in
         *(f32x4 *)((float *)e.C + m * e.ldc + n) = f32x4{v0, v1, v2, v3};
     } else {
         uint2 out;
-        out.x = pack_bf16x2(v0, v1);
-        out.y = pack_bf16x2(v2, v3);
+        out.x = pack_c16x2(v0, v1, e.c_f16);
+        out.y = pack_c16x2(v2, v3, e.c_f16);
         *(uint2 *)((uint16_t *)e.C + m * e.ldc + n) = out;
     }
 }

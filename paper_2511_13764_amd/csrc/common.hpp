@@ -10,7 +10,8 @@ namespace brg {
 // One fully validated problem: C = act(beta*C + sum_i A_i x B_i + bias)
 // (input/output statement of Algorithm 1; Section 6 for bias and ReLU).
 struct Problem {
-    int in_bf16;            // 1: A, B are bf16 bit patterns; 0: fp32
+    int in_bf16;            // 1: A, B are bf16 bit patterns
+    int in_f16;             // 1: A, B are IEEE binary16 bit patterns (both 0: fp32)
     int transA, transB;     // 1: stored transposed (K x M / N x K), row-major
     int64_t M, N, K, batch;
     const void *A;          // base of every A_i
@@ -26,7 +27,7 @@ struct Problem {
     float beta;
     void *C;
     int64_t ldc;
-    int c_f32;              // 1: C is fp32; 0: bf16
+    int c_f32;              // 1: C is fp32; 0: the 16-bit type of the operands (bf16 / binary16)
     const float *bias;      // nullptr or N fp32 values
     int relu;
     // Reduction split: the flattened (batch x k-block) iteration space is cut into
@@ -68,12 +69,35 @@ __device__ __forceinline__ float bf16_to_f32(uint16_t h)
     return __uint_as_float((uint32_t)h << 16);
 }
 
+// binary16 (the FP16 of Section 2.2): hardware conversions, round to nearest even on
+// narrowing, subnormals kept.
+__device__ __forceinline__ float f16_to_f32(uint16_t h)
+{
+    return (float)__builtin_bit_cast(_Float16, h);
+}
+__device__ __forceinline__ uint16_t f32_to_f16_rne(float f)
+{
+    return __builtin_bit_cast(uint16_t, (_Float16)f);
+}
+__device__ __forceinline__ uint32_t pack_f16x2(float lo, float hi)
+{
+    return (uint32_t)f32_to_f16_rne(lo) | ((uint32_t)f32_to_f16_rne(hi) << 16);
+}
+// 16-bit C element of either kind.
+__device__ __forceinline__ float c16_to_f32(uint16_t h, int f16) { return f16 ? f16_to_f32(h) : bf16_to_f32(h); }
+__device__ __forceinline__ uint32_t pack_c16x2(float lo, float hi, int f16)
+{
+    return f16 ? pack_f16x2(lo, hi) : pack_bf16x2(lo, hi);
+}
+
+
 // Epilogue parameters as the kernels see them.
 struct Epilogue {
     float beta;
     void *C;
     int64_t ldc;
     int c_f32;
+    int c_f16;              // with c_f32 == 0: 1 = binary16 C, 0 = bf16 C
     const float *bias;
     int relu;
 };
@@ -84,7 +108,7 @@ __device__ __forceinline__ float epilogue_value(const Epilogue &e, float v, int6
 {
     if (e.beta != 0.0f) {
         float old = e.c_f32 ? ((const float *)e.C)[m * e.ldc + n]
-                            : bf16_to_f32(((const uint16_t *)e.C)[m * e.ldc + n]);
+                            : c16_to_f32(((const uint16_t *)e.C)[m * e.ldc + n], e.c_f16);
         v = fmaf(e.beta, old, v);
     }
     if (e.bias)
@@ -100,8 +124,10 @@ __device__ __forceinline__ void epilogue_store(const Epilogue &e, float v, int64
     if (e.c_f32)
         ((float *)e.C)[m * e.ldc + n] = v;
     else
-        ((uint16_t *)e.C)[m * e.ldc + n] = f32_to_bf16_rne(v);
+        ((uint16_t *)e.C)[m * e.ldc + n] = e.c_f16 ? f32_to_f16_rne(v) : f32_to_bf16_rne(v);
 }
+
+inline bool in_16bit(const Problem &p) { return p.in_bf16 || p.in_f16; }
 
 // ---- launchers (each returns the hipError_t of its launch) -------------------
 

@@ -19,15 +19,18 @@ constexpr int GT = 64;      // tile edge (M and N)
 constexpr int GK = 16;      // k-block
 constexpr int GPAD = 1;     // LDS row padding (floats)
 
-template <bool BF16>
+// KIND: 0 fp32, 1 bf16, 2 binary16
+template <int KIND>
 __device__ __forceinline__ float load_in(const void *p, int64_t idx)
 {
-    if (BF16)
+    if (KIND == 1)
         return bf16_to_f32(((const uint16_t *)p)[idx]);
+    if (KIND == 2)
+        return f16_to_f32(((const uint16_t *)p)[idx]);
     return ((const float *)p)[idx];
 }
 
-template <bool BF16>
+template <int KIND>
 __global__ void __launch_bounds__(256)
 generic_kernel(int transA, int transB, int64_t M, int64_t N, int64_t K, int64_t batch,
                const void *A, const int64_t *A_off, int64_t lda,
@@ -68,7 +71,7 @@ generic_kernel(int transA, int transB, int64_t M, int64_t N, int64_t K, int64_t 
             const int64_t gm = m0 + m, gk = k0 + k;
             float v = 0.0f;
             if (gm < M && gk < K)
-                v = load_in<BF16>(A, ao + (transA ? gk * lda + gm : gm * lda + gk));
+                v = load_in<KIND>(A, ao + (transA ? gk * lda + gm : gm * lda + gk));
             As[k][m] = v;
         }
         for (int e = tid; e < GT * GK; e += 256) {
@@ -77,7 +80,7 @@ generic_kernel(int transA, int transB, int64_t M, int64_t N, int64_t K, int64_t 
             const int64_t gn = n0 + n, gk = k0 + k;
             float v = 0.0f;
             if (gn < N && gk < K)
-                v = load_in<BF16>(B, bo + (transB == 2 ? (gk >> 3) * ldb + gn * 8 + (gk & 7)
+                v = load_in<KIND>(B, bo + (transB == 2 ? (gk >> 3) * ldb + gn * 8 + (gk & 7)
                                                        : transB ? gn * ldb + gk : gk * ldb + gn));
             Bs[k][n] = v;
         }
@@ -155,6 +158,7 @@ static Epilogue make_epilogue(const Problem &p)
     e.C = p.C;
     e.ldc = p.ldc;
     e.c_f32 = p.c_f32;
+    e.c_f16 = p.in_f16;
     e.bias = p.bias;
     e.relu = p.relu;
     return e;
@@ -164,18 +168,21 @@ hipError_t launch_generic(const Problem &p)
 {
     dim3 grid((unsigned)((p.N + GT - 1) / GT), (unsigned)((p.M + GT - 1) / GT), (unsigned)p.split);
     // A batched call runs one launch per matrix here (this is the slow general path).
-    const int64_t esz = p.in_bf16 ? 2 : 4, csz = p.c_f32 ? 4 : 2;
+    const int64_t esz = in_16bit(p) ? 2 : 4, csz = p.c_f32 ? 4 : 2;
     for (int64_t z = 0; z < p.nmat; ++z) {
         Epilogue e = make_epilogue(p);
         e.C = (char *)p.C + z * p.ms_c * csz;
         const void *A = (const char *)p.A + z * p.ms_a * esz;
         const void *B = (const char *)p.B + z * p.ms_b * esz;
         if (p.in_bf16)
-            hipLaunchKernelGGL(generic_kernel<true>, grid, dim3(256), 0, p.stream, p.transA,
+            hipLaunchKernelGGL(generic_kernel<1>, grid, dim3(256), 0, p.stream, p.transA,
                                p.b_packed ? 2 : p.transB, p.M, p.N, p.K, p.batch, A, p.A_off, p.lda, B, p.B_off,
                                p.ldb, e, p.split, p.partial);
+        else if (p.in_f16)
+            hipLaunchKernelGGL(generic_kernel<2>, grid, dim3(256), 0, p.stream, p.transA, p.transB, p.M, p.N,
+                               p.K, p.batch, A, p.A_off, p.lda, B, p.B_off, p.ldb, e, p.split, p.partial);
         else
-            hipLaunchKernelGGL(generic_kernel<false>, grid, dim3(256), 0, p.stream, p.transA, p.transB, p.M, p.N,
+            hipLaunchKernelGGL(generic_kernel<0>, grid, dim3(256), 0, p.stream, p.transA, p.transB, p.M, p.N,
                                p.K, p.batch, A, p.A_off, p.lda, B, p.B_off, p.ldb, e, p.split, p.partial);
         hipError_t err = hipGetLastError();
         if (err != hipSuccess)
