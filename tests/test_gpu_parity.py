@@ -402,3 +402,45 @@ def test_pingpong_and_f32_edge_tiles_with_skipped_wave_loads(oracle, tA, tB):
         ref = H.oracle_gemm_case(oracle, case)
         out, _ = H.run_gemm_case(case, force=(names.index(vname), 1))
         assert H.rel_fro(H.widen(out), ref) <= 1e-5, vname
+
+
+@pytest.mark.gpu
+def test_seeded_random_shape_sweep(oracle):
+    """120 seeded random problems (all dtypes, transposes, beta, padded leading dimensions,
+    sizes chosen around the tile edges 16 / 32 / 64 / 128 / 256 and k-blocks 32 / 64) through
+    the automatic plan, each against the oracle."""
+    rng = np.random.default_rng(20251113)
+    edges = [1, 8, 15, 16, 17, 31, 32, 33, 63, 64, 65, 96, 127, 128, 129, 136, 200, 255, 256, 257, 264, 384, 520]
+    kvals = [1, 8, 31, 32, 33, 64, 96, 128, 192, 320, 448, 640, 1088]
+    seen = set()
+    for it in range(120):
+        dtype = ["bf16", "f32", "bf16"][it % 3]
+        tA, tB = int(rng.integers(0, 2)), int(rng.integers(0, 2))
+        M, N, K = int(rng.choice(edges)), int(rng.choice(edges)), int(rng.choice(kvals))
+        if rng.random() < 0.5:          # keep the tuned kernels in play half of the time
+            M, N, K = (M + 7) // 8 * 8, (N + 7) // 8 * 8, (K + 63) // 64 * 64
+        pad = int(rng.choice([0, 0, 8, 3]))
+        beta = float(rng.choice([0.0, 1.0, -0.5]))
+        c_f32 = dtype == "f32" or bool(rng.integers(0, 2))
+        ra, ca = (K, M) if tA else (M, K)
+        rb, cb = (N, K) if tB else (K, N)
+        A = np.full((ra, ca + pad), np.nan, np.float32)
+        Bm = np.full((rb, cb + pad), np.nan, np.float32)
+        A[:, :ca] = W.normal_f32(200 + it, 0, (ra, ca))
+        Bm[:, :cb] = W.normal_f32(200 + it, 1, (rb, cb))
+        C0 = W.normal_f32(200 + it, 2, (M, N)) if beta != 0.0 else None
+        if dtype == "bf16":
+            A, Bm = W.to_bf16_bits(A), W.to_bf16_bits(Bm)
+        if C0 is not None and not c_f32:
+            C0 = W.to_bf16_bits(C0)
+        case = W.GemmCase(f"sweep{it}_{dtype}_{M}x{N}x{K}_t{tA}{tB}_pad{pad}_b{beta}", dtype, M, N, K, tA, tB, beta,
+                          A, Bm, C0, c_f32)
+        say(case.name)
+        out, _ = H.run_gemm_case(case, ldc=N + pad, workspace_bytes=B.gemm_workspace_bytes(1, M, N, K))
+        seen.add(B.gemm_variant_name(B.gemm_last_variant()))
+        ref = H.oracle_gemm_case(oracle, case)
+        got = H.widen(out)
+        assert np.isfinite(got).all(), case.name
+        tol = 1e-5 if c_f32 else (H.TOL_BF16 if M * N >= 4096 else 4e-3)
+        assert H.rel_fro(got, ref) <= tol, (case.name, B.gemm_variant_name(B.gemm_last_variant()))
+    assert len(seen) >= 5, seen
