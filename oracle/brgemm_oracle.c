@@ -297,3 +297,35 @@ int oracle_pack_vnni(int v, int transB, int64_t K, int64_t N, const uint16_t *B,
         }
     return 0;
 }
+
+/*
+ * int8 matrix multiplication with exact integer accumulation (Section 2.2 names INT8
+ * among the packed types; Section 5(c): other types follow the same structure):
+ *
+ *     out[m][n] = (accumulate ? C0[m][n] : 0) + sum_k A(m,k) * B(k,n)
+ *
+ * A and B are signed 8-bit, read through transA / transB / lda / ldb exactly as in
+ * oracle_brgemm; C0 is int32; the sum is formed in int64 (no wrap-around is possible
+ * for K < 2^31) and returned as int64, so a 32-bit overflow of the true result shows
+ * up as a value outside the int32 range rather than being hidden.
+ * Returns 0, or -1 on a bad argument.
+ */
+int oracle_gemm_s8(int transA, int transB, int64_t M, int64_t N, int64_t K,
+                   const int8_t *A, int64_t lda, const int8_t *B, int64_t ldb,
+                   int accumulate, const int32_t *C0, int64_t ldc0, int64_t *out)
+{
+    if (M < 0 || N < 0 || K < 0 || (accumulate && !C0))
+        return -1;
+#pragma omp parallel for schedule(static)
+    for (int64_t m = 0; m < M; ++m)
+        for (int64_t n = 0; n < N; ++n) {
+            int64_t s = accumulate ? (int64_t)C0[m * ldc0 + n] : 0;
+            for (int64_t k = 0; k < K; ++k) {
+                const int64_t a = transA ? A[k * lda + m] : A[m * lda + k];
+                const int64_t b = transB ? B[n * ldb + k] : B[k * ldb + n];
+                s += a * b;
+            }
+            out[m * N + n] = s;
+        }
+    return 0;
+}

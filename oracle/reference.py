@@ -50,6 +50,8 @@ def _load():
     lib.oracle_f16_to_f64.argtypes = [ctypes.c_uint16]
     lib.oracle_num_threads.restype = cint
     lib.oracle_num_threads.argtypes = []
+    lib.oracle_gemm_s8.restype = cint
+    lib.oracle_gemm_s8.argtypes = [cint, cint, i64, i64, i64, vp, i64, vp, i64, cint, vp, i64, vp]
     lib.oracle_pack_vnni.restype = cint
     lib.oracle_pack_vnni.argtypes = [cint, cint, i64, i64, vp, i64, i64, i64, vp]
     _lib = lib
@@ -181,4 +183,26 @@ def pack_vnni(B, ldb, K, N, v, *, transB=0, k_rows=None, n_pitch=None):
     rc = _load().oracle_pack_vnni(v, int(transB), K, N, _ptr(B), ldb, k_rows, n_pitch, _ptr(out))
     if rc != 0:
         raise ValueError("oracle_pack_vnni rejected its arguments")
+    return out
+
+
+def gemm_s8_ref(A, lda, B, ldb, M, N, K, *, transA=0, transB=0, C0=None, ldc0=None):
+    """Exact int64 reference of the int8 product (plus an int32 C0 when given)."""
+    A = np.ascontiguousarray(A, dtype=np.int8)
+    B = np.ascontiguousarray(B, dtype=np.int8)
+    if M and K and ((K - 1) * lda + M if transA else (M - 1) * lda + K) > A.size:
+        raise ValueError("A out of bounds")
+    if N and K and ((N - 1) * ldb + K if transB else (K - 1) * ldb + N) > B.size:
+        raise ValueError("B out of bounds")
+    acc = C0 is not None
+    if acc:
+        C0 = np.ascontiguousarray(C0, dtype=np.int32)
+        ldc0 = N if ldc0 is None else ldc0
+        if M and N and (M - 1) * ldc0 + N > C0.size:
+            raise ValueError("C0 out of bounds")
+    out = np.empty((M, N), dtype=np.int64)
+    rc = _load().oracle_gemm_s8(int(transA), int(transB), M, N, K, _ptr(A), lda, _ptr(B), ldb, int(acc),
+                                _ptr(C0) if acc else ctypes.c_void_p(0), int(ldc0 or 0), _ptr(out))
+    if rc != 0:
+        raise ValueError("oracle_gemm_s8 rejected its arguments")
     return out

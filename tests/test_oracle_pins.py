@@ -527,3 +527,39 @@ def test_f16_gemm_small_integers_and_statistics(oracle):
     ref = oracle.gemm_ref(A, 300, Bm, 48, 64, 48, 300, beta=0.5, C0=C0, ldc0=48)
     lib = 0.5 * C0.astype(np.float64) + A.astype(np.float64) @ Bm.astype(np.float64)
     assert np.abs(ref - lib).max() <= 1e-12 * np.abs(lib).max()
+
+
+# ---------------------------------------------------------------- int8 (Section 2.2 names INT8)
+
+def test_s8_literal_extremes_and_library(oracle):
+    # [[1,-2],[3,4]] x [[-5,6],[7,-8]] = [[-19,22],[13,-14]]  (worked by hand)
+    A = np.array([[1, -2], [3, 4]], dtype=np.int8)
+    Bm = np.array([[-5, 6], [7, -8]], dtype=np.int8)
+    assert oracle.gemm_s8_ref(A, 2, Bm, 2, 2, 2, 2).tolist() == [[-19, 22], [13, -14]]
+    # extremes: (-128)^2 * K and -128 * 127 * K, closed form
+    K = 1000
+    A = np.full((3, K), -128, np.int8)
+    Bm = np.full((K, 2), -128, np.int8)
+    Bm[:, 1] = 127
+    assert oracle.gemm_s8_ref(A, K, Bm, 2, 3, 2, K).tolist() == [[16384 * K, -128 * 127 * K]] * 3
+    # random, all transposes, padded leading dimensions, accumulate: against numpy's int64 matmul
+    rng = np.random.default_rng(21)
+    M, N, K = 13, 9, 70
+    Al = rng.integers(-128, 128, (M, K)).astype(np.int8)
+    Bl = rng.integers(-128, 128, (K, N)).astype(np.int8)
+    C0 = rng.integers(-2 ** 31, 2 ** 31, (M, N + 2)).astype(np.int32)
+    want = Al.astype(np.int64) @ Bl.astype(np.int64)
+    for tA in (0, 1):
+        for tB in (0, 1):
+            As = np.full((K, M + 3) if tA else (M, K + 3), 55, np.int8)
+            Bs = np.full((N, K + 5) if tB else (K, N + 5), -77, np.int8)
+            As[:, :(M if tA else K)] = Al.T if tA else Al
+            Bs[:, :(K if tB else N)] = Bl.T if tB else Bl
+            got = oracle.gemm_s8_ref(As, As.shape[1], Bs, Bs.shape[1], M, N, K, transA=tA, transB=tB)
+            assert (got == want).all(), (tA, tB)
+            got = oracle.gemm_s8_ref(As, As.shape[1], Bs, Bs.shape[1], M, N, K, transA=tA, transB=tB,
+                                     C0=C0, ldc0=N + 2)
+            assert (got == want + C0[:, :N].astype(np.int64)).all(), (tA, tB)
+    # identity
+    I = np.eye(K, dtype=np.int8)
+    assert (oracle.gemm_s8_ref(Al, K, I, K, M, K, K) == Al).all()
