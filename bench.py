@@ -216,6 +216,14 @@ def main():
                lambda: B.gemm_f16(0, 0, 4096, 4096, 4096, a, 4096, b, 4096, 0.0, c, 4096, 0, workspace=ws), PEAK_BF16,
                steps=100)
         del a, b, c
+        # int8 operands, int32 results (NT: both operands k-contiguous); peak 5.0 POP/s dense int8
+        a = torch.randint(-128, 128, (4096, 4096), device="cuda", dtype=torch.int8)
+        b = torch.randint(-128, 128, (4096, 4096), device="cuda", dtype=torch.int8)
+        c = torch.empty((4096, 4096), device="cuda", dtype=torch.int32)
+        record("s8_4096_nt", 2.0 * 4096 ** 3,
+               lambda: B.gemm_s8(0, 1, 4096, 4096, 4096, a, 4096, b, 4096, 0, c, 4096), 5033.2, steps=100)
+        others["s8_4096_nt"]["unit"] = "TOP/s (tflops / frac_mfma_peak fields), against 5033.2 TOP/s int8 MFMA"
+        del a, b, c
         # MLP shapes, weights stored N x K
         # The skinny cases are bound by the stream of the 90 MB weight matrix, which fits
         # the 256 MB last-level cache: "warm" repeats one matrix, "cold" rotates over four

@@ -107,6 +107,20 @@ int gemm_f16(int transA, int transB, int64_t M, int64_t N, int64_t K,
              void *workspace, size_t workspace_bytes, void *stream);
 
 /*
+ * int8 GEMM with exact int32 accumulation (Section 2.2 names INT8 among the packed
+ * types; Section 5(c)):  C[M,N] = (accumulate ? C : 0) + A[M,K] x B[K,N].
+ * A, B: device, signed 8-bit; C: device, int32; lda/ldb/ldc in elements.  Sums wrap
+ * modulo 2^32 like any int32 arithmetic (|sum| < 2^31 needs K <= 131071 in the worst
+ * case).  The matrix-instruction kernels take the "NT" layout (transA == 0,
+ * transB == 1: both operands contiguous in k) with K a multiple of 128, 16-byte
+ * aligned bases and leading dimensions that are multiples of 16; every other layout,
+ * size or alignment runs on a plain integer kernel with identical results.
+ */
+int gemm_s8(int transA, int transB, int64_t M, int64_t N, int64_t K,
+            const int8_t *A, int64_t lda, const int8_t *B, int64_t ldb,
+            int accumulate, int32_t *C, int64_t ldc, void *stream);
+
+/*
  * bf16 batch-reduce GEMM into an fp32 C (Algorithm 1 as a whole; Section 2.1:
  * the source tiles need not be contiguous).  Tile i of A starts at element
  * A_base + A_off[i], tile i of B at B_base + B_off[i]; M, N, K, lda, ldb and

@@ -142,6 +142,19 @@ int gemm_f16(int transA, int transB, int64_t M, int64_t N, int64_t K,
     return run(p, workspace, workspace_bytes, false);
 }
 
+int gemm_s8(int transA, int transB, int64_t M, int64_t N, int64_t K,
+            const int8_t *A, int64_t lda, const int8_t *B, int64_t ldb,
+            int accumulate, int32_t *C, int64_t ldc, void *stream)
+{
+    Problem p{};
+    p.in_s8 = 1; p.transA = transA; p.transB = transB;
+    p.M = M; p.N = N; p.K = K; p.batch = 1;
+    p.A = A; p.lda = lda; p.B = B; p.ldb = ldb;
+    p.beta = accumulate ? 1.0f : 0.0f; p.C = C; p.ldc = ldc; p.c_f32 = 1;
+    p.stream = (hipStream_t)stream;
+    return run(p, nullptr, 0, false);
+}
+
 int brgemm_bf16(int transA, int transB, int64_t M, int64_t N, int64_t K, int64_t batch,
                 const uint16_t *A_base, const int64_t *A_off, int64_t lda,
                 const uint16_t *B_base, const int64_t *B_off, int64_t ldb,

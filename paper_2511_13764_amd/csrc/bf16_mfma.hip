@@ -27,7 +27,7 @@
 
 namespace brg {
 
-template <int BM, int BN, bool A_KMAJ, int B_LAY, bool F16>
+template <int BM, int BN, bool A_KMAJ, int B_LAY, int KIND>
 __global__ void __launch_bounds__(256)
 bf16_mfma_kernel(Bf16Args p)
 {
@@ -157,7 +157,7 @@ bf16_mfma_kernel(Bf16Args p)
         for (int a = 0; a < TN; ++a)
 #pragma unroll
             for (int b = 0; b < TM; ++b)
-                acc[a][b] = mfma_32x32x16<F16>(fb[buf][a], fa[buf][b], acc[a][b]);
+                acc[a][b] = mfma_32x32x16<KIND>(fb[buf][a], fa[buf][b], acc[a][b]);
     };
 
     if (n_iter > 0) {
@@ -224,16 +224,17 @@ static hipError_t launch_tile(const Problem &p)
     const bool ak = p.transA == 0;
     const int lay = p.b_packed ? LAY_PACKED : (p.transB == 1 ? LAY_K : LAY_MN);
     void (*kern)(Bf16Args) = nullptr;
-#define BRG_PICK(F16)                                                                        \
-    if (ak && lay == LAY_K) kern = bf16_mfma_kernel<BM, BN, true, LAY_K, F16>;                \
-    else if (ak && lay == LAY_MN) kern = bf16_mfma_kernel<BM, BN, true, LAY_MN, F16>;         \
-    else if (ak) kern = bf16_mfma_kernel<BM, BN, true, LAY_PACKED, F16>;                      \
-    else if (lay == LAY_K) kern = bf16_mfma_kernel<BM, BN, false, LAY_K, F16>;                \
-    else if (lay == LAY_MN) kern = bf16_mfma_kernel<BM, BN, false, LAY_MN, F16>;              \
-    else kern = bf16_mfma_kernel<BM, BN, false, LAY_PACKED, F16>;
-    if (p.in_f16) { BRG_PICK(true) } else { BRG_PICK(false) }
+#define BRG_PICK(KIND)                                                                        \
+    if (ak && lay == LAY_K) kern = bf16_mfma_kernel<BM, BN, true, LAY_K, KIND>;                \
+    else if (ak && lay == LAY_MN) kern = bf16_mfma_kernel<BM, BN, true, LAY_MN, KIND>;         \
+    else if (ak) kern = bf16_mfma_kernel<BM, BN, true, LAY_PACKED, KIND>;                      \
+    else if (lay == LAY_K) kern = bf16_mfma_kernel<BM, BN, false, LAY_K, KIND>;                \
+    else if (lay == LAY_MN) kern = bf16_mfma_kernel<BM, BN, false, LAY_MN, KIND>;              \
+    else kern = bf16_mfma_kernel<BM, BN, false, LAY_PACKED, KIND>;
+    if (p.in_s8) kern = bf16_mfma_kernel<BM, BN, true, LAY_K, KIND_S8>;
+    else if (p.in_f16) { BRG_PICK(KIND_F16) } else { BRG_PICK(KIND_BF16) }
 #undef BRG_PICK
-    static thread_local const void *configured[24] = {nullptr};
+    static thread_local const void *configured[13] = {nullptr};
     bool done = false;
     for (const void *c : configured)
         done = done || c == (const void *)kern;
@@ -253,6 +254,13 @@ hipError_t launch_bf16_128x128(const Problem &p) { return launch_tile<128, 128>(
 // Alignment and shape rules of the kernels in this file.
 bool bf16_mfma_eligible(const Problem &p)
 {
+    if (p.in_s8) {
+        // int8: both operands k-contiguous, whole 128-byte k-rows, 16-byte aligned rows
+        return p.transA == 0 && p.transB == 1 && p.batch == 1 && !p.A_off && !p.B_off && p.nmat == 1 &&
+               p.K % 128 == 0 && !((uintptr_t)p.A & 15) && !((uintptr_t)p.B & 15) && !(p.lda & 15) &&
+               !(p.ldb & 15) && p.lda < (1 << 23) && p.ldb < (1 << 23) && p.K / 128 < ((int64_t)1 << 31) &&
+               p.M * p.N < ((int64_t)1 << 40);
+    }
     if (!in_16bit(p))
         return false;
     if (p.K % BK != 0)

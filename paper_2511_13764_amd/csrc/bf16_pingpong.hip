@@ -53,7 +53,7 @@ __device__ __forceinline__ void phase_sync()
 // offsets that are not 16-byte aligned).  EDGE: the tile overhangs the matrix in the
 // direction this wave loads, so lanes outside it are switched off.  Both are uniform
 // over the workgroup / wave and chosen once, so the loop body carries no branches for them.
-template <bool A_KMAJ, int B_LAY, bool DIRECT, bool EDGE, bool F16>
+template <bool A_KMAJ, int B_LAY, bool DIRECT, bool EDGE, int KIND>
 __device__ __forceinline__ void pp_body(const Bf16Args &p)
 {
     // Load duty: waves 0-3 fetch the B halves, waves 4-7 the A halves (8 wave-loads
@@ -200,7 +200,7 @@ __device__ __forceinline__ void pp_body(const Bf16Args &p)
             for (int a = 0; a < PP_TN; ++a)
 #pragma unroll
                 for (int b = 0; b < PP_TM; ++b)
-                    acc[a][b] = mfma_16x16x32<F16>(fb[st][a], fa[st][b], acc[a][b]);
+                    acc[a][b] = mfma_16x16x32<KIND>(fb[st][a], fa[st][b], acc[a][b]);
     };
 
     if (n_iter > 0) {
@@ -267,8 +267,8 @@ __device__ __forceinline__ void pp_body(const Bf16Args &p)
                 const int row = 16 * bb + (lane & 15);
                 const int col = 16 * a + 4 * (lane >> 4);
                 const f32x4 v = acc[a][2 * b2 + bb];
-                const u32x2 pk = {F16 ? pack_f16x2(v[0], v[1]) : pack_bf16x2(v[0], v[1]),
-                                  F16 ? pack_f16x2(v[2], v[3]) : pack_bf16x2(v[2], v[3])};
+                const u32x2 pk = {KIND == KIND_F16 ? pack_f16x2(v[0], v[1]) : pack_bf16x2(v[0], v[1]),
+                                  KIND == KIND_F16 ? pack_f16x2(v[2], v[3]) : pack_bf16x2(v[2], v[3])};
                 *(LDS_AS u32x2 *)(stage_h + row * 136 + col * 2) = pk;
             });
             asm volatile("" ::: "memory");
@@ -315,7 +315,7 @@ __device__ __forceinline__ void pp_body(const Bf16Args &p)
     });
 }
 
-template <bool A_KMAJ, int B_LAY, bool F16>
+template <bool A_KMAJ, int B_LAY, int KIND>
 __global__ void __launch_bounds__(512)
 bf16_pingpong_kernel(Bf16Args p)
 {
@@ -352,11 +352,11 @@ bf16_pingpong_kernel(Bf16Args p)
     const bool edge = (w >> 2) ? ((int64_t)(tm + 1) * PP_BM > p.M)
                                : (B_LAY != LAY_PACKED && (int64_t)(tn + 1) * PP_BN > p.N);
     if (direct) {
-        if (!edge) pp_body<A_KMAJ, B_LAY, true, false, F16>(p);
-        else pp_body<A_KMAJ, B_LAY, true, true, F16>(p);
+        if (!edge) pp_body<A_KMAJ, B_LAY, true, false, KIND>(p);
+        else pp_body<A_KMAJ, B_LAY, true, true, KIND>(p);
     } else {
-        if (!edge) pp_body<A_KMAJ, B_LAY, false, false, F16>(p);
-        else pp_body<A_KMAJ, B_LAY, false, true, F16>(p);
+        if (!edge) pp_body<A_KMAJ, B_LAY, false, false, KIND>(p);
+        else pp_body<A_KMAJ, B_LAY, false, true, KIND>(p);
     }
 }
 
@@ -371,16 +371,17 @@ static hipError_t launch_pp(const Problem &p)
     const bool ak = p.transA == 0;
     const int lay = p.b_packed ? LAY_PACKED : (p.transB == 1 ? LAY_K : LAY_MN);
     void (*kern)(Bf16Args) = nullptr;
-#define BRG_PICK(F16)                                                                \
-    if (ak && lay == LAY_K) kern = bf16_pingpong_kernel<true, LAY_K, F16>;            \
-    else if (ak && lay == LAY_MN) kern = bf16_pingpong_kernel<true, LAY_MN, F16>;     \
-    else if (ak) kern = bf16_pingpong_kernel<true, LAY_PACKED, F16>;                  \
-    else if (lay == LAY_K) kern = bf16_pingpong_kernel<false, LAY_K, F16>;            \
-    else if (lay == LAY_MN) kern = bf16_pingpong_kernel<false, LAY_MN, F16>;          \
-    else kern = bf16_pingpong_kernel<false, LAY_PACKED, F16>;
-    if (p.in_f16) { BRG_PICK(true) } else { BRG_PICK(false) }
+#define BRG_PICK(KIND)                                                                \
+    if (ak && lay == LAY_K) kern = bf16_pingpong_kernel<true, LAY_K, KIND>;            \
+    else if (ak && lay == LAY_MN) kern = bf16_pingpong_kernel<true, LAY_MN, KIND>;     \
+    else if (ak) kern = bf16_pingpong_kernel<true, LAY_PACKED, KIND>;                  \
+    else if (lay == LAY_K) kern = bf16_pingpong_kernel<false, LAY_K, KIND>;            \
+    else if (lay == LAY_MN) kern = bf16_pingpong_kernel<false, LAY_MN, KIND>;          \
+    else kern = bf16_pingpong_kernel<false, LAY_PACKED, KIND>;
+    if (p.in_s8) kern = bf16_pingpong_kernel<true, LAY_K, KIND_S8>;
+    else if (p.in_f16) { BRG_PICK(KIND_F16) } else { BRG_PICK(KIND_BF16) }
 #undef BRG_PICK
-    static thread_local const void *configured[12] = {nullptr};
+    static thread_local const void *configured[13] = {nullptr};
     bool done = false;
     for (const void *c : configured)
         done = done || c == (const void *)kern;

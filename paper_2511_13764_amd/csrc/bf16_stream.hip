@@ -25,7 +25,7 @@ namespace {
 constexpr int ST_BN = 128;
 constexpr int ST_STAGES = 3;
 
-template <int BM, bool A_KMAJ, int B_LAY, bool F16>
+template <int BM, bool A_KMAJ, int B_LAY, int KIND>
 __global__ void __launch_bounds__(256)
 bf16_stream_kernel(Bf16Args p)
 {
@@ -127,7 +127,7 @@ bf16_stream_kernel(Bf16Args p)
             for (int a = 0; a < TN; ++a)
 #pragma unroll
                 for (int b = 0; b < TM; ++b)
-                    acc[a][b] = mfma_16x16x32<F16>(fb[st][a], fa[st][b], acc[a][b]);
+                    acc[a][b] = mfma_16x16x32<KIND>(fb[st][a], fa[st][b], acc[a][b]);
         // The fragments are in registers before the next barrier lets another wave's
         // loads overwrite this slot.
         wait_lgkmcnt0();
@@ -147,20 +147,22 @@ hipError_t launch_stream(const Problem &p)
     const dim3 grid((unsigned)(a.tiles_m * a.tiles_n), (unsigned)p.split, (unsigned)p.nmat);
     const size_t lds = (size_t)ST_STAGES * (BM + ST_BN) * BK * 2;
     void (*kern)(Bf16Args) = nullptr;
-#define BRG_PICK(AK, F16)                                                                    \
-    kern = p.b_packed ? bf16_stream_kernel<BM, AK, LAY_PACKED, F16>                           \
-           : p.transB == 1 ? bf16_stream_kernel<BM, AK, LAY_K, F16> : bf16_stream_kernel<BM, AK, LAY_MN, F16>;
-    if (p.transA == 0) {
-        if (p.in_f16) { BRG_PICK(true, true) } else { BRG_PICK(true, false) }
+#define BRG_PICK(AK, KIND)                                                                    \
+    kern = p.b_packed ? bf16_stream_kernel<BM, AK, LAY_PACKED, KIND>                           \
+           : p.transB == 1 ? bf16_stream_kernel<BM, AK, LAY_K, KIND> : bf16_stream_kernel<BM, AK, LAY_MN, KIND>;
+    if (p.in_s8) {
+        kern = bf16_stream_kernel<BM, true, LAY_K, KIND_S8>;
+    } else if (p.transA == 0) {
+        if (p.in_f16) { BRG_PICK(true, KIND_F16) } else { BRG_PICK(true, KIND_BF16) }
     } else {
         if constexpr (BM == 128) {
-            if (p.in_f16) { BRG_PICK(false, true) } else { BRG_PICK(false, false) }
+            if (p.in_f16) { BRG_PICK(false, KIND_F16) } else { BRG_PICK(false, KIND_BF16) }
         } else {
             return hipErrorInvalidValue;
         }
     }
 #undef BRG_PICK
-    static thread_local const void *configured[12] = {nullptr};
+    static thread_local const void *configured[13] = {nullptr};
     bool done = false;
     for (const void *c : configured)
         done = done || c == (const void *)kern;

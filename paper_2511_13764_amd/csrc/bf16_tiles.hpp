@@ -15,21 +15,32 @@ typedef __attribute__((ext_vector_type(8))) short s16x8;
 
 typedef __attribute__((ext_vector_type(8))) _Float16 f16x8;
 
-// The matrix instruction for either 16-bit operand type (fragments travel as bf16x8
-// registers; only the instruction differs).
-template <bool F16>
+typedef __attribute__((ext_vector_type(4))) int i32x4;
+typedef __attribute__((ext_vector_type(16))) int i32x16;
+
+// The matrix instruction per operand kind.  Fragments travel as 16-byte registers
+// (bf16x8) whatever they hold; for int8 the same 16 bytes are 16 k-values, the
+// instruction contracts 64 (resp. 32) of them per step and the accumulators hold
+// int32 bit patterns in the same registers.
+template <int KIND>
 __device__ __forceinline__ f32x4 mfma_16x16x32(bf16x8 a, bf16x8 b, f32x4 c)
 {
-    if constexpr (F16)
+    if constexpr (KIND == KIND_F16)
         return __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(f16x8, a), __builtin_bit_cast(f16x8, b), c, 0, 0, 0);
+    else if constexpr (KIND == KIND_S8)
+        return __builtin_bit_cast(f32x4, __builtin_amdgcn_mfma_i32_16x16x64_i8(__builtin_bit_cast(i32x4, a), __builtin_bit_cast(i32x4, b),
+                                                                            __builtin_bit_cast(i32x4, c), 0, 0, 0));
     else
         return __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, c, 0, 0, 0);
 }
-template <bool F16>
+template <int KIND>
 __device__ __forceinline__ f32x16 mfma_32x32x16(bf16x8 a, bf16x8 b, f32x16 c)
 {
-    if constexpr (F16)
+    if constexpr (KIND == KIND_F16)
         return __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(f16x8, a), __builtin_bit_cast(f16x8, b), c, 0, 0, 0);
+    else if constexpr (KIND == KIND_S8)
+        return __builtin_bit_cast(f32x16, __builtin_amdgcn_mfma_i32_32x32x32_i8(__builtin_bit_cast(i32x4, a), __builtin_bit_cast(i32x4, b),
+                                                                             __builtin_bit_cast(i32x16, c), 0, 0, 0));
     else
         return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
 }
@@ -66,10 +77,14 @@ __device__ __forceinline__ void select_matrix(Bf16Args &p)
 // Host side: fill the fields every bf16 launcher shares.
 inline void fill_common_args(Bf16Args &a, const Problem &p)
 {
-    a.M = p.M; a.N = p.N; a.K = p.K; a.batch = p.batch;
-    a.A = (const uint16_t *)p.A; a.A_off = p.A_off; a.lda = p.lda;
-    a.B = (const uint16_t *)p.B; a.B_off = p.B_off; a.ldb = p.ldb;
+    // The kernels address their operands in 2-byte units along k; an int8 problem (both
+    // operands k-contiguous) is handed over with K and the leading dimensions halved.
+    const int64_t u = p.in_s8 ? 2 : 1;
+    a.M = p.M; a.N = p.N; a.K = p.K / u; a.batch = p.batch;
+    a.A = (const uint16_t *)p.A; a.A_off = p.A_off; a.lda = p.lda / u;
+    a.B = (const uint16_t *)p.B; a.B_off = p.B_off; a.ldb = p.ldb / u;
     a.epi.beta = p.beta; a.epi.C = p.C; a.epi.ldc = p.ldc; a.epi.c_f32 = p.c_f32; a.epi.c_f16 = p.in_f16;
+    a.epi.c_i32 = p.in_s8;
     a.epi.bias = p.bias; a.epi.relu = p.relu;
     a.split = p.split; a.partial = p.partial;
     a.ms_a = p.ms_a; a.ms_b = p.ms_b; a.ms_c = p.ms_c;
@@ -431,6 +446,13 @@ __device__ __forceinline__ void store4_epilogue(const Epilogue &e, int64_t m, in
 {
     if (left <= 0)
         return;
+    if (e.c_i32 && vec && left >= 4) {
+        i32x4 r = {__float_as_int(v0), __float_as_int(v1), __float_as_int(v2), __float_as_int(v3)};
+        if (e.beta != 0.0f)
+            r += *(const i32x4 *)((const int32_t *)e.C + m * e.ldc + n);
+        *(i32x4 *)((int32_t *)e.C + m * e.ldc + n) = r;
+        return;
+    }
     if (!(vec && left >= 4)) {
         epilogue_store(e, v0, m, n);
         if (left > 1) epilogue_store(e, v1, m, n + 1);

@@ -11,7 +11,8 @@ namespace brg {
 // (input/output statement of Algorithm 1; Section 6 for bias and ReLU).
 struct Problem {
     int in_bf16;            // 1: A, B are bf16 bit patterns
-    int in_f16;             // 1: A, B are IEEE binary16 bit patterns (both 0: fp32)
+    int in_f16;             // 1: A, B are IEEE binary16 bit patterns
+    int in_s8;              // 1: A, B are signed 8-bit integers, C is int32 (all three 0: fp32)
     int transA, transB;     // 1: stored transposed (K x M / N x K), row-major
     int64_t M, N, K, batch;
     const void *A;          // base of every A_i
@@ -98,6 +99,8 @@ struct Epilogue {
     int64_t ldc;
     int c_f32;
     int c_f16;              // with c_f32 == 0: 1 = binary16 C, 0 = bf16 C
+    int c_i32;              // 1: C is int32 and the accumulators hold int32 bit patterns
+                            // (int8 path; beta is 0 or 1 and means "add the old C")
     const float *bias;
     int relu;
 };
@@ -120,6 +123,13 @@ __device__ __forceinline__ float epilogue_value(const Epilogue &e, float v, int6
 
 __device__ __forceinline__ void epilogue_store(const Epilogue &e, float v, int64_t m, int64_t n)
 {
+    if (e.c_i32) {
+        int32_t r = __float_as_int(v);
+        if (e.beta != 0.0f)
+            r += ((const int32_t *)e.C)[m * e.ldc + n];
+        ((int32_t *)e.C)[m * e.ldc + n] = r;
+        return;
+    }
     v = epilogue_value(e, v, m, n);
     if (e.c_f32)
         ((float *)e.C)[m * e.ldc + n] = v;
@@ -128,6 +138,9 @@ __device__ __forceinline__ void epilogue_store(const Epilogue &e, float v, int64
 }
 
 inline bool in_16bit(const Problem &p) { return p.in_bf16 || p.in_f16; }
+// Operand kinds as template arguments of the kernels that move 128-byte k-rows.
+constexpr int KIND_BF16 = 0, KIND_F16 = 1, KIND_S8 = 2;
+inline int kind_of(const Problem &p) { return p.in_s8 ? KIND_S8 : p.in_f16 ? KIND_F16 : KIND_BF16; }
 
 // ---- launchers (each returns the hipError_t of its launch) -------------------
 
@@ -139,6 +152,8 @@ hipError_t launch_reduce(const Problem &p);
 hipError_t launch_scale_only(const Problem &p);
 // VNNI-v packing of a K x N matrix of 16-bit elements into k_rows / v groups of
 // n_pitch columns (zero outside the matrix).
+// Any-layout int8 GEMM into int32 (plain integer loop; the fallback of the int8 path).
+hipError_t launch_generic_s8(const Problem &p);
 hipError_t launch_pack_vnni(int v, int transB, int64_t K, int64_t N, const uint16_t *B, int64_t ldb,
                             int64_t k_rows, int64_t n_pitch, uint16_t *out, hipStream_t stream);
 

@@ -126,7 +126,7 @@ int choose_plan(const Problem &p, size_t workspace_bytes, int forced_variant, in
 {
     Plan plan{V_GENERIC, 1};
     // A batched call (nmat matrices) multiplies the tile count and never splits.
-    const bool single = p.nmat == 1;
+    const bool single = p.nmat == 1 && !p.in_s8;     // int8 sums are not split (the reduction adds floats)
     const int skinny_bm = p.M <= 32 ? 32 : p.M <= 64 ? 64 : 128;
     if (p.M <= 128 && bf16_stream_eligible(p, skinny_bm)) {
         // Few rows of A: the time goes into streaming B once.
@@ -169,7 +169,7 @@ int choose_plan(const Problem &p, size_t workspace_bytes, int forced_variant, in
 hipError_t launch_variant(int v, const Problem &p)
 {
     switch (v) {
-    case V_GENERIC: return launch_generic(p);
+    case V_GENERIC: return p.in_s8 ? launch_generic_s8(p) : launch_generic(p);
     case V_BF16_128x128: return launch_bf16_128x128(p);
     case V_BF16_PP256: return launch_bf16_pingpong(p);
     case V_F32_128x128: return launch_f32_128x128(p);

@@ -290,7 +290,7 @@ hipError_t launch_f32_128x128(const Problem &p)
     a.M = p.M; a.N = p.N; a.K = p.K;
     a.A = (const float *)p.A; a.lda = p.lda;
     a.B = (const float *)p.B; a.ldb = p.ldb;
-    a.epi.beta = p.beta; a.epi.C = p.C; a.epi.ldc = p.ldc; a.epi.c_f32 = 1; a.epi.c_f16 = 0;
+    a.epi.beta = p.beta; a.epi.C = p.C; a.epi.ldc = p.ldc; a.epi.c_f32 = 1; a.epi.c_f16 = 0; a.epi.c_i32 = 0;
     a.epi.bias = p.bias; a.epi.relu = p.relu;
     a.split = p.split; a.partial = p.partial;
     a.ms_a = p.ms_a; a.ms_b = p.ms_b; a.ms_c = p.ms_c;
@@ -325,7 +325,7 @@ hipError_t launch_f32_128x128(const Problem &p)
 // its extent a multiple of 4 (whole 16-byte chunks).
 bool f32_mfma_eligible(const Problem &p)
 {
-    if (in_16bit(p) || !p.c_f32 || p.A_off || p.batch != 1)
+    if (in_16bit(p) || p.in_s8 || !p.c_f32 || p.A_off || p.batch != 1)
         return false;
     if (p.K % FK != 0)
         return false;

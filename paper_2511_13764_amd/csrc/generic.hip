@@ -159,6 +159,7 @@ static Epilogue make_epilogue(const Problem &p)
     e.ldc = p.ldc;
     e.c_f32 = p.c_f32;
     e.c_f16 = p.in_f16;
+    e.c_i32 = p.in_s8;
     e.bias = p.bias;
     e.relu = p.relu;
     return e;
@@ -189,6 +190,35 @@ hipError_t launch_generic(const Problem &p)
             return err;
     }
     return hipSuccess;
+}
+
+// int8 x int8 -> int32, one C element per thread, any layout: the int8 fallback.
+__global__ void __launch_bounds__(256)
+generic_s8_kernel(int transA, int transB, int64_t M, int64_t N, int64_t K, const int8_t *A, int64_t lda,
+                  const int8_t *B, int64_t ldb, int accumulate, int32_t *C, int64_t ldc)
+{
+    const int64_t n = (int64_t)blockIdx.x * 16 + (threadIdx.x & 15);
+    const int64_t m = (int64_t)blockIdx.y * 16 + (threadIdx.x >> 4);
+    if (m >= M || n >= N)
+        return;
+    int32_t s = accumulate ? C[m * ldc + n] : 0;
+    for (int64_t k = 0; k < K; ++k) {
+        const int32_t a = transA ? A[k * lda + m] : A[m * lda + k];
+        const int32_t b = transB ? B[n * ldb + k] : B[k * ldb + n];
+        s += a * b;
+    }
+    C[m * ldc + n] = s;
+}
+
+hipError_t launch_generic_s8(const Problem &p)
+{
+    if ((p.M + 15) / 16 > 65535)
+        return hipErrorInvalidValue;
+    const dim3 grid((unsigned)((p.N + 15) / 16), (unsigned)((p.M + 15) / 16));
+    hipLaunchKernelGGL(generic_s8_kernel, grid, dim3(256), 0, p.stream, p.transA, p.transB, p.M, p.N, p.K,
+                       (const int8_t *)p.A, p.lda, (const int8_t *)p.B, p.ldb, p.beta != 0.0f ? 1 : 0,
+                       (int32_t *)p.C, p.ldc);
+    return hipGetLastError();
 }
 
 static unsigned elementwise_grid(int64_t total)

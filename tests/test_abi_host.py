@@ -168,3 +168,14 @@ def test_batched_argument_rules(lib):
         assert call(**kw) == B.INVALID_ARG, kw
     assert B.gemm_f32_batched(0, 0, 4, 8, 16, 2, P, 16, 64, P, 8, 128, 0.0, P, 8, 3, stream=0, check=False) == \
         B.INVALID_ARG                                  # C matrices would overlap
+
+
+def test_s8_argument_rules(lib):
+    def call(**kw):
+        a = dict(tA=0, tB=1, M=4, N=8, K=128, A=P, lda=128, B=P, ldb=128, acc=0, C=P, ldc=8)
+        a.update(kw)
+        return B.gemm_s8(a["tA"], a["tB"], a["M"], a["N"], a["K"], a["A"], a["lda"], a["B"], a["ldb"], a["acc"],
+                         a["C"], a["ldc"], stream=0, check=False)
+    assert call(M=0) == B.OK and call(N=0) == B.OK
+    for kw in (dict(M=-1), dict(K=-1), dict(tA=2), dict(lda=127), dict(ldb=127), dict(ldc=7), dict(A=0), dict(C=0)):
+        assert call(**kw) == B.INVALID_ARG, kw
