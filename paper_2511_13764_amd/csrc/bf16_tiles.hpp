@@ -148,11 +148,6 @@ __device__ __forceinline__ void load16_to_lds_saddr(const char *base, uint32_t l
                  : "m0");
 }
 
-__device__ __forceinline__ void load16_to_lds(const uint16_t *g, uint32_t lds_byte, LDS_AS char *lds0)
-{
-    __builtin_amdgcn_global_load_lds((const GLB_AS void *)g, (LDS_AS void *)(lds0 + lds_byte), 16, 0, 0);
-}
-
 // ---------------------------------------------------------------------------
 // Operand tile whose contiguous direction is k ("K-major": A with transA == 0,
 // B with transB == 1).  LDS image: row r (an m or n index) takes 128 bytes; its
@@ -166,19 +161,10 @@ struct KMajorTile {
     static constexpr int kInstr = ROWS / 8;          // wave-instructions per tile
     static constexpr int kPerWave = kInstr / NW;
 
-    // Global element offset (relative to the tile's k-block origin) this lane fetches
-    // for wave-instruction j of wave w.  row_limit clamps ragged edges to a valid row.
-    __device__ static int64_t src_offset(int w, int j, int lane, int64_t row0, int64_t row_limit, int64_t ld)
-    {
-        const int g = w * kPerWave + j;
-        int64_t row = row0 + 8 * g + (lane >> 3);
-        row = row < row_limit ? row : row_limit - 1;
-        const int c = (lane & 7) ^ (((8 * g + (lane >> 3)) >> 1) & 7);
-        return row * ld + 8 * c;
-    }
     __device__ static uint32_t dst_byte(int w, int j) { return (uint32_t)(w * kPerWave + j) * 1024u; }
-    // The same source position as a 32-bit byte offset from the tile origin
-    // (row row0, first k of the block): lets the load use a uniform base + lane offset.
+    // What this lane fetches for wave-instruction j of wave w, as a 32-bit byte offset
+    // from the tile origin (row row0, first k of the block): lets the load use a uniform
+    // base + lane offset.  row_limit redirects rows past a ragged edge to a valid row.
     __device__ static uint32_t src_rel_bytes(int w, int j, int lane, int64_t row0, int64_t row_limit, int64_t ld)
     {
         const int g = w * kPerWave + j;
@@ -249,16 +235,6 @@ struct MNMajorTile {
 
     __device__ static int swz(int kr) { return ((kr & 3) << 2) | (((kr >> 3) & 1) << 1); }
 
-    __device__ static int64_t src_offset(int w, int j, int lane, int64_t col0, int64_t col_limit, int64_t ld)
-    {
-        const int idx = (w * kPerWave + j) * 64 + lane;
-        const int kr = idx / kChunksPerRow;
-        const int pc = idx % kChunksPerRow;
-        const int c = pc ^ swz(kr);
-        int64_t col = col0 + 8 * c;
-        col = col < col_limit ? col : col0;           // chunk wholly outside: any valid chunk
-        return (int64_t)kr * ld + col;
-    }
     __device__ static uint32_t dst_byte(int w, int j) { return (uint32_t)(w * kPerWave + j) * 1024u; }
     __device__ static uint32_t src_rel_bytes(int w, int j, int lane, int64_t col0, int64_t col_limit, int64_t ld)
     {
