@@ -7,9 +7,9 @@
 // fp32 MFMA runs at 1/16 of the bf16 rate, so per k-block the 64 MFMAs of a SIMD
 // take ~4096 cycles against 32 KiB of loads and ~100 KiB of LDS reads per CU: the
 // kernel is bound by the matrix pipe; two waves per SIMD cover each other's load
-// issue and LDS latency, and a three-stage LDS ring gives every load a whole k-block
-// of time to land.  Global -> LDS copies
-// use the scalar-base form of global_load_lds_dwordx4, spread between the MFMA groups.
+// issue and LDS latency, and a three-stage LDS ring with its one barrier per block in
+// mid-block gives every load a whole k-block of time to land.  Global -> LDS copies
+// use the scalar-base form of global_load_lds_dwordx4, threaded between the MFMAs.
 //
 // LDS images.  An operand whose contiguous direction is k keeps 128-byte rows with
 // the 16-byte chunk c of row r at position c ^ ((r >> 1) & 7) (same image as the
@@ -174,27 +174,74 @@ f32_mfma_kernel(F32Args p)
             }
         }
     };
-    // 8 * TN MFMAs.  Operands swapped (B first): the 32x32 result is C^T, so a lane owns
-    // row m = lane%32 and 4 consecutive columns per group of 4 registers.
-    auto mma_step = [&](int buf) {
+    // The same reads one at a time (unit u: the A tiles first, then the B tiles), so
+    // that they can be placed between individual MFMAs.
+    constexpr int UA = A_KMAJ ? 2 : 8, UB = B_KMAJ ? TN : 4 * TN, UNITS = UA + UB;
+    auto read_unit = [&](int stage, int j, int buf, auto uc) {
+        constexpr int u = decltype(uc)::value;
+        LDS_AS char *at = smem + (uint32_t)stage * F_STAGE;
+        LDS_AS char *bt = at + F_OP_BYTES;
+        if constexpr (u < UA) {
+            if constexpr (A_KMAJ)
+                fa[buf][u] = *(LDS_AS f32x4 *)(at + FKTile::frag_byte(wm * 64, u, j, lane));
+            else
+                fa[buf][u / 4][u % 4] = FMNTile::read(at, wm * 64, u / 4, j, u % 4, lane);
+        } else {
+            constexpr int v = u - UA;
+            if constexpr (B_KMAJ)
+                fb[buf][v] = *(LDS_AS f32x4 *)(bt + FKTile::frag_byte(wn * WN, v, j, lane));
+            else
+                fb[buf][v / 4][v % 4] = FMNTile::read(bt, wn * WN, v / 4, j, v % 4, lane);
+        }
+    };
+    // One j-step: 8 * TN MFMAs with this wave's other work threaded between them.  An
+    // MFMA holds the pipe for 64 cycles after it issues, so whatever the wave issues
+    // right behind it is free; done in a clump after the last MFMA it would leave the
+    // pipe idle (the other wave of the SIMD runs the same code at the same time).  After
+    // MFMA 0: a quarter of the loads for block it + 2; after MFMAs 1..: the fragment reads
+    // of step j + 1, spread evenly.  Operands swapped (B first): the 32x32 result is C^T,
+    // so a lane owns row m = lane%32 and 4 consecutive columns per group of 4 registers.
+    constexpr int NM = 8 * TN;
+    constexpr int L = 2 * PER_OP;               // loads per wave per block
+    auto step = [&](int cur, int nxt, auto jc, bool has_next, bool more, int fill) {
+        constexpr int j = decltype(jc)::value;
+        constexpr int buf = j & 1;
+        static_for<0, NM>([&](auto ic) {
+            constexpr int idx = decltype(ic)::value;
+            constexpr int e = idx / (2 * TN), a = (idx / 2) % TN, b = idx % 2;
+            acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x2f32(fb[buf][a][e], fa[buf][b][e], acc[a][b], 0, 0, 0);
+            if constexpr (j >= 2 && (idx == 0 || idx == NM / 2)) {
+                // second half of the block: the loads of block it + 2, L / 4 at a time
+                if (more) {
 #pragma unroll
-        for (int e = 0; e < 4; ++e)
-#pragma unroll
-            for (int a = 0; a < TN; ++a)
-#pragma unroll
-                for (int b = 0; b < 2; ++b)
-                    acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x2f32(fb[buf][a][e], fa[buf][b][e], acc[a][b], 0, 0, 0);
+                    for (int q = 0; q < L / 4; ++q)
+                        issue_one(fill, ((j - 2) * 2 + (idx == 0 ? 0 : 1)) * (L / 4) + q);
+                }
+            }
+            if constexpr (idx > 0) {
+                // the fragment reads of the next step (of the next block after step 3)
+                static_for<0, UNITS>([&](auto uc) {
+                    if constexpr (1 + decltype(uc)::value * (NM - 1) / UNITS == idx) {
+                        if constexpr (j < 3)
+                            read_unit(cur, j + 1, buf ^ 1, uc);
+                        else if (has_next)
+                            read_unit(nxt, 0, buf ^ 1, uc);
+                    }
+                });
+            }
+            __builtin_amdgcn_sched_barrier(0);
+        });
     };
 
-    // Three LDS stages: while block `it` is multiplied the loads of block it + 2 are
-    // issued (a quarter after each group of MFMAs) into the stage that block it - 1
-    // occupied, and the barrier that ends the block only waits for block it + 1, which
-    // was requested a whole block (~4000 cycles) earlier.
-    // Counting outstanding loads is only valid when every load is really issued: on a
-    // tile that overhangs the matrix a wave-load whose lanes are all switched off is
-    // skipped, so such tiles wait for everything instead.
-    constexpr int L = 2 * PER_OP;               // loads per wave per block
-    const bool counted = m0 + FB <= p.M && n0 + FB <= p.N;
+    // Three LDS stages and one barrier per k-block, placed in the MIDDLE of the block:
+    // after the first two of its four 8-deep steps a wave waits for its loads of block
+    // it + 1 (requested during the second half of block it - 1, a whole block of time
+    // ago, and the only loads outstanding at that point - so the wait is a plain
+    // vmcnt(0) and needs no counting) and the barrier publishes block it + 1 and proves
+    // block it - 1 fully read.  The second half of block `it` requests block it + 2 into
+    // the slot of block it - 1 and, under its last MFMAs, already reads the first
+    // fragments of block it + 1: neither LDS latency nor a barrier sits between the last
+    // MFMA of one block and the first of the next.
     if (n_iter > 0) {
 #pragma unroll
         for (int q = 0; q < L; ++q)
@@ -205,43 +252,30 @@ f32_mfma_kernel(F32Args p)
             for (int q = 0; q < L; ++q)
                 issue_one(1, q);
             advance();
-            if (counted)
-                wait_vmcnt_le<L>();
-            else
-                wait_vmcnt0();
-        } else {
-            wait_vmcnt0();
         }
+        wait_vmcnt0();
         block_sync();
+        read_step(0, 0, 0);
+        __builtin_amdgcn_sched_barrier(0);
 
         int cur = 0;
         for (int it = 0; it < n_iter; ++it) {
-            const int fill = cur == 0 ? 2 : cur - 1;        // (cur + 2) % 3
+            const int nxt = cur == 2 ? 0 : cur + 1;
+            const int fill = cur == 0 ? 2 : cur - 1;        // slot of block it - 1 = slot of block it + 2
             const bool more = it + 2 < n_iter;
-            read_step(cur, 0, 0);
-#pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                if (j < 3)
-                    read_step(cur, j + 1, (j + 1) & 1);
-                mma_step(j & 1);
-                __builtin_amdgcn_sched_barrier(0);
-                if (more) {
-#pragma unroll
-                    for (int q = 0; q < PER_OP / 2; ++q)
-                        issue_one(fill, j * (PER_OP / 2) + q);
-                }
-                __builtin_amdgcn_sched_barrier(0);
-            }
+            const bool has_next = it + 1 < n_iter;
+            step(cur, nxt, std::integral_constant<int, 0>{}, has_next, more, fill);
+            step(cur, nxt, std::integral_constant<int, 1>{}, has_next, more, fill);
+            wait_vmcnt0();                      // block it + 1 (nothing younger is in flight here)
+            block_sync();
+            step(cur, nxt, std::integral_constant<int, 2>{}, has_next, more, fill);
+            step(cur, nxt, std::integral_constant<int, 3>{}, has_next, more, fill);
             if (more)
                 advance();
-            if (more && counted)
-                wait_vmcnt_le<L>();             // block it + 1 has landed; it + 2 may fly
-            else
-                wait_vmcnt0();
-            wait_lgkmcnt0();
-            block_sync();
-            cur = cur == 2 ? 0 : cur + 1;
+            cur = nxt;
         }
+        wait_lgkmcnt0();
+        block_sync();                           // every wave is done with the LDS stages
     }
 
     // ---- epilogue: beta*C, bias, ReLU, store (or raw partial tile for a split).
