@@ -5,7 +5,7 @@
 // grids of at most 256 tiles of 128 x 128 (one workgroup per CU anyway), where the
 // third stage hides the load latency that the two-stage 4-wave kernel exposes.
 //
-// A workgroup of 4 wavefronts owns a BM x 128 block of C (BM = 32, 64 or 128) and
+// A workgroup of 4 or 8 wavefronts owns a BM x 128 block of C (BM = 32, 64 or 128) and
 // walks its share of K in 64-deep blocks.  What matters here is how many bytes are
 // in flight per CU, so the LDS is a ring of three stages, each holding one k-block
 // of A and B: the loads for block t + 2 are requested while block t is multiplied,
@@ -25,14 +25,22 @@ namespace {
 constexpr int ST_BN = 128;
 constexpr int ST_STAGES = 3;
 
+// Waves per workgroup: 8 (two per SIMD) for the 128- and 64-row tiles - twice as many
+// waves issuing the global->LDS loads raises what one CU can pull (measured 77-96
+// against 57 B/ns) and these shapes are bound by exactly that; 4 for the 32-row tile,
+// whose A block is only 4 wave-loads.
+template <int BM>
+struct StreamWaves { static constexpr int value = BM >= 64 ? 8 : 4; };
+
 template <int BM, bool A_KMAJ, int B_LAY, int KIND>
-__global__ void __launch_bounds__(256)
+__global__ void __launch_bounds__(StreamWaves<BM>::value * 64)
 bf16_stream_kernel(Bf16Args p)
 {
+    constexpr int NW = StreamWaves<BM>::value;
     static_assert(A_KMAJ || BM == 128, "an m-contiguous A needs the 128-row tile");
-    typedef typename TileOf<BM, 4, A_KMAJ ? LAY_K : LAY_MN>::type ATile;
-    typedef typename TileOf<ST_BN, 4, B_LAY>::type BTile;
-    constexpr int WGM = BM == 128 ? 2 : 1, WGN = 4 / WGM;     // wave grid
+    typedef typename TileOf<BM, NW, A_KMAJ ? LAY_K : LAY_MN>::type ATile;
+    typedef typename TileOf<ST_BN, NW, B_LAY>::type BTile;
+    constexpr int WGM = BM == 128 ? 2 : 1, WGN = NW / WGM;    // wave grid
     constexpr int WM = BM / WGM, WN = ST_BN / WGN;
     constexpr int TM = WM / 16, TN = WN / 16;                 // 16x16 MFMA tiles per wave
     constexpr uint32_t A_BYTES = BM * BK * 2, B_BYTES = ST_BN * BK * 2;
@@ -173,7 +181,7 @@ hipError_t launch_stream(const Problem &p)
         for (auto &c : configured)
             if (!c) { c = (const void *)kern; break; }
     }
-    hipLaunchKernelGGL(kern, grid, dim3(256), lds, p.stream, a);
+    hipLaunchKernelGGL(kern, grid, dim3(StreamWaves<BM>::value * 64), lds, p.stream, a);
     return hipGetLastError();
 }
 
