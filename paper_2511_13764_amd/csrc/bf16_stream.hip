@@ -61,10 +61,12 @@ bf16_stream_kernel(Bf16Args p)
     const int tm = (int)blockIdx.x % p.tiles_m, tn = (int)blockIdx.x / p.tiles_m;
     const int64_t m0 = (int64_t)tm * BM, n0 = (int64_t)tn * ST_BN;
 
+    // Reduction range of this workgroup: flattened (batch, k-block) iterations.
     const int kblocks = (int)(p.K / BK);
-    const int per = (kblocks + p.split - 1) / p.split;
+    const int total = (int)p.batch * kblocks;
+    const int per = (total + p.split - 1) / p.split;
     const int it_begin = (int)blockIdx.y * per;
-    const int it_end = (it_begin + per < kblocks) ? it_begin + per : kblocks;
+    const int it_end = (it_begin + per < total) ? it_begin + per : total;
     const int n_iter = it_end > it_begin ? it_end - it_begin : 0;
 
     // Rows / columns past the edge of the matrix are redirected to a valid one (their
@@ -79,21 +81,63 @@ bf16_stream_kernel(Bf16Args p)
         b_src[j] = BTile::src_rel_bytes(w, j, lane, n0, p.N, p.ldb);
     const int64_t b_kstep = BTile::kstep(p.ldb);
     const int64_t a_kstep = ATile::kstep(p.lda);
-    const uint16_t *ld_a = uniform_ptr(p.A + ATile::origin(m0, p.lda) + (int64_t)it_begin * a_kstep);
-    const uint16_t *ld_b = uniform_ptr(p.B + BTile::origin(n0, p.ldb) + (int64_t)it_begin * b_kstep);
+    const int64_t a_origin = ATile::origin(m0, p.lda), b_origin = BTile::origin(n0, p.ldb);
+    // Load cursor: (batch index, k-block) of the next block to request and its pointers.
+    int ld_i = n_iter > 0 ? it_begin / kblocks : 0;
+    int ld_kb = n_iter > 0 ? it_begin - ld_i * kblocks : 0;
+    const uint16_t *ld_a = uniform_ptr(p.A + (p.A_off ? p.A_off[ld_i] : 0) + a_origin + ld_kb * a_kstep);
+    const uint16_t *ld_b = uniform_ptr(p.B + (p.B_off ? p.B_off[ld_i] : 0) + b_origin + ld_kb * b_kstep);
     int ld_slot = 0;
+    // Tile offsets live in device memory: if one is not a multiple of 8 elements the
+    // whole workgroup stages its blocks through registers with 2-byte loads instead
+    // (same LDS image; those loads complete before the stores, so the counted waits
+    // below simply find nothing outstanding).
+    bool direct = true;
+    if (p.A_off) {
+        int ok = 1;
+        for (int i = tid; i < (int)p.batch; i += NW * 64)
+            ok &= (((p.A_off[i] | p.B_off[i]) & 7) == 0);
+        direct = __syncthreads_and(ok) != 0;
+    }
+    auto staged16 = [&](const char *gc, uint32_t lds_byte) {
+        const uint16_t *g = (const uint16_t *)gc;
+        s16x8 v;
+#pragma unroll
+        for (int e = 0; e < 8; ++e)
+            v[e] = (short)g[e];
+        *(LDS_AS s16x8 *)(smem + lds_byte + lane * 16) = v;
+    };
 
     auto issue_loads = [&]() {
         const uint32_t base = (uint32_t)ld_slot * STAGE;
+        if (direct) {
 #pragma unroll
-        for (int j = 0; j < BTile::kPerWave; ++j)
-            load16_to_lds_saddr((const char *)ld_b, b_src[j],
-                                (uint32_t)(size_t)(smem + base + A_BYTES + BTile::dst_byte(w, j)));
+            for (int j = 0; j < BTile::kPerWave; ++j)
+                load16_to_lds_saddr((const char *)ld_b, b_src[j],
+                                    (uint32_t)(size_t)(smem + base + A_BYTES + BTile::dst_byte(w, j)));
 #pragma unroll
-        for (int j = 0; j < ATile::kPerWave; ++j)
-            load16_to_lds_saddr((const char *)ld_a, a_src[j], (uint32_t)(size_t)(smem + base + ATile::dst_byte(w, j)));
-        ld_a += a_kstep;
-        ld_b += b_kstep;
+            for (int j = 0; j < ATile::kPerWave; ++j)
+                load16_to_lds_saddr((const char *)ld_a, a_src[j],
+                                    (uint32_t)(size_t)(smem + base + ATile::dst_byte(w, j)));
+        } else {
+#pragma unroll
+            for (int j = 0; j < BTile::kPerWave; ++j)
+                staged16((const char *)ld_b + b_src[j], base + A_BYTES + BTile::dst_byte(w, j));
+#pragma unroll
+            for (int j = 0; j < ATile::kPerWave; ++j)
+                staged16((const char *)ld_a + a_src[j], base + ATile::dst_byte(w, j));
+        }
+        if (++ld_kb == kblocks) {
+            ld_kb = 0;
+            ++ld_i;
+            if (p.A_off && ld_i < (int)p.batch) {
+                ld_a = uniform_ptr(p.A + p.A_off[ld_i] + a_origin);
+                ld_b = uniform_ptr(p.B + p.B_off[ld_i] + b_origin);
+            }
+        } else {
+            ld_a += a_kstep;
+            ld_b += b_kstep;
+        }
         ld_slot = ld_slot + 1 == stages ? 0 : ld_slot + 1;
     };
     f32x4 acc[TN][TM];
@@ -114,6 +158,8 @@ bf16_stream_kernel(Bf16Args p)
             wait_vmcnt_le<(ST_STAGES - 2) * L>();
         else
             wait_vmcnt0();                          // tail: fewer blocks than slots remain
+        if (!direct)
+            wait_lgkmcnt0();                        // register-staged blocks: their LDS stores
         block_sync();
         if (t + ahead < n_iter)
             issue_loads();                          // into the slot read in iteration t - 1
@@ -197,11 +243,11 @@ hipError_t launch_bf16_stream(const Problem &p, int bm)
     }
 }
 
-// Plain GEMM; the 32- and 64-row tiles need A stored M x K (k contiguous), the 128-row
-// tile takes either order; B in any layout.
+// The 32- and 64-row tiles need A stored M x K (k contiguous), the 128-row tile takes
+// either order; B in any layout; batch-reduce with tile offsets included.
 bool bf16_stream_eligible(const Problem &p, int bm)
 {
-    return bf16_mfma_eligible(p) && (p.transA == 0 || bm == 128) && p.batch == 1 && !p.A_off && !p.B_off;
+    return bf16_mfma_eligible(p) && (p.transA == 0 || bm == 128);
 }
 
 }  // namespace brg

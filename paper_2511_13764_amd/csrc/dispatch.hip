@@ -78,7 +78,7 @@ static int split_for_small_grid(const Problem &p, size_t workspace_bytes)
 static int split_for_stream(const Problem &p, int bm, size_t workspace_bytes)
 {
     const int64_t tiles = ((p.M + bm - 1) / bm) * ((p.N + 127) / 128);
-    const int64_t kblocks = p.K / 64;
+    const int64_t kblocks = p.batch * (p.K / 64);
     const double per_split = 0.75 * bm / 32.0;
     int best = 1;
     double best_cost = 1e30;
