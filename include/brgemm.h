@@ -232,6 +232,16 @@ int gemm_last_hip_error(void);
  */
 int gemm_force_variant(int variant, int split);
 
+/*
+ * The shape -> tile table (Section 5(a): tile sizes are chosen per shape by rule): which
+ * kernel variant and reduction split a plain or batch-reduce call of this element type
+ * (BRGEMM_DTYPE_*), layout, size and leading dimensions would take, assuming 16-byte
+ * aligned operands and `workspace_bytes` of workspace.  Pure host logic: nothing is
+ * launched and no GPU is needed.  variant, split: host, receive the plan.
+ */
+int gemm_query_plan(int dtype, int transA, int transB, int64_t M, int64_t N, int64_t K, int64_t batch,
+                    int64_t lda, int64_t ldb, size_t workspace_bytes, int *variant, int *split);
+
 /* Name of variant number v ("" past the end): lets a harness enumerate them. */
 const char *gemm_variant_name(int v);
 

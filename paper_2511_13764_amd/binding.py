@@ -30,7 +30,7 @@ EXPORTS = ["gemm_f32", "gemm_bf16", "brgemm_bf16", "brgemm_fused", "gemm_workspa
            "gemm_strerror", "gemm_last_hip_error", "gemm_force_variant", "gemm_variant_name",
            "gemm_last_variant", "gemm_last_split", "gemm_mfma_probe", "gemm_pack_vnni_bf16",
            "gemm_packed_b_bytes", "gemm_pack_b_bf16", "gemm_bf16_packed", "gemm_bf16_batched",
-           "gemm_f32_batched", "gemm_f16", "gemm_s8"]
+           "gemm_f32_batched", "gemm_f16", "gemm_s8", "gemm_query_plan"]
 
 _lib = None
 
@@ -91,6 +91,9 @@ def load():
     lib.gemm_bf16_batched.argtypes = [ci, ci, i64, i64, i64, i64, vp, i64, i64, vp, i64, i64, cf, vp, i64, i64, ci, vp]
     lib.gemm_f32_batched.restype = ci
     lib.gemm_f32_batched.argtypes = [ci, ci, i64, i64, i64, i64, vp, i64, i64, vp, i64, i64, cf, vp, i64, i64, vp]
+    lib.gemm_query_plan.restype = ci
+    lib.gemm_query_plan.argtypes = [ci, ci, ci, i64, i64, i64, i64, i64, i64, sz, ctypes.POINTER(ci),
+                                    ctypes.POINTER(ci)]
     lib.gemm_mfma_probe.restype = ci
     lib.gemm_mfma_probe.argtypes = [ci, vp, i64, ci, vp, ctypes.POINTER(ctypes.c_double), vp]
     _lib = lib
@@ -208,6 +211,18 @@ def gemm_f32_batched(transA, transB, M, N, K, nmat, A, lda, strideA, B, ldb, str
     rc = load().gemm_f32_batched(transA, transB, M, N, K, nmat, _ptr(A), lda, strideA, _ptr(B), ldb, strideB,
                                  beta, _ptr(C), ldc, strideC, _stream(stream))
     return _check(rc, "gemm_f32_batched", check)
+
+
+def gemm_query_plan(dtype, transA, transB, M, N, K, batch=1, lda=None, ldb=None, workspace_bytes=1 << 40):
+    """(variant name, split) the automatic plan picks; host logic only."""
+    lda = (M if transA else K) if lda is None else lda
+    ldb = (K if transB else N) if ldb is None else ldb
+    v, s = ctypes.c_int(-1), ctypes.c_int(0)
+    rc = load().gemm_query_plan(dtype, transA, transB, M, N, K, batch, lda, ldb, workspace_bytes,
+                                ctypes.byref(v), ctypes.byref(s))
+    if rc != OK:
+        raise BrgemmError(rc, "gemm_query_plan")
+    return gemm_variant_name(v.value), s.value
 
 
 def gemm_mfma_probe(dtype, operands, iters, blocks, sink, stream=None, check=True):

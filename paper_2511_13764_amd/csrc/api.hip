@@ -339,6 +339,31 @@ int gemm_force_variant(int variant, int split)
     return BRGEMM_OK;
 }
 
+int gemm_query_plan(int dtype, int transA, int transB, int64_t M, int64_t N, int64_t K, int64_t batch,
+                    int64_t lda, int64_t ldb, size_t workspace_bytes, int *variant, int *split)
+{
+    if (dtype != BRGEMM_DTYPE_F32 && dtype != BRGEMM_DTYPE_BF16 && dtype != BRGEMM_DTYPE_F16)
+        return BRGEMM_INVALID_ARG;
+    if ((transA | 1) != 1 || (transB | 1) != 1 || M <= 0 || N <= 0 || K <= 0 || batch <= 0 || !variant || !split)
+        return BRGEMM_INVALID_ARG;
+    Problem p{};
+    p.in_bf16 = dtype == BRGEMM_DTYPE_BF16; p.in_f16 = dtype == BRGEMM_DTYPE_F16;
+    p.transA = transA; p.transB = transB; p.M = M; p.N = N; p.K = K; p.batch = batch; p.nmat = 1;
+    // stand-ins for 16-byte aligned operands (never dereferenced); batch > 1 means tile offsets
+    p.A = (const void *)0x1000; p.B = (const void *)0x1000; p.C = (void *)0x1000;
+    p.A_off = batch > 1 ? (const int64_t *)0x1000 : nullptr; p.B_off = p.A_off;
+    p.lda = lda; p.ldb = ldb; p.ldc = N; p.c_f32 = 1;
+    if (p.lda < stored_cols_a(p) || p.ldb < stored_cols_b(p))
+        return BRGEMM_INVALID_ARG;
+    Plan plan;
+    const int rc = choose_plan(p, workspace_bytes, -1, 0, &plan);
+    if (rc != BRGEMM_OK)
+        return rc;
+    *variant = plan.variant;
+    *split = plan.split;
+    return BRGEMM_OK;
+}
+
 const char *gemm_variant_name(int v) { return variant_name(v); }
 int gemm_last_variant(void) { return tl_last_variant; }
 int gemm_last_split(void) { return tl_last_split; }

@@ -179,3 +179,42 @@ def test_s8_argument_rules(lib):
     assert call(M=0) == B.OK and call(N=0) == B.OK
     for kw in (dict(M=-1), dict(K=-1), dict(tA=2), dict(lda=127), dict(ldb=127), dict(ldc=7), dict(A=0), dict(C=0)):
         assert call(**kw) == B.INVALID_ARG, kw
+
+
+def test_shape_to_tile_table(lib):
+    """The automatic plan for the named configurations and around its crossovers (host logic)."""
+    q = B.gemm_query_plan
+    BF, F32, F16 = B.DTYPE_BF16, B.DTYPE_F32, B.DTYPE_F16
+    assert q(BF, 0, 0, 4096, 4096, 4096) == ("bf16_pingpong_256x256x64", 1)
+    assert q(BF, 0, 0, 8192, 8192, 8192) == ("bf16_pingpong_256x256x64", 1)
+    assert q(F16, 0, 0, 4096, 4096, 4096) == ("bf16_pingpong_256x256x64", 1)
+    assert q(BF, 0, 1, 4096, 11008, 4096) == ("bf16_pingpong_256x256x64", 1)
+    assert q(BF, 0, 1, 4096, 4096, 11008) == ("bf16_pingpong_256x256x64", 1)
+    # skinny M: streaming kernels, split from rounds x k-blocks
+    assert q(BF, 0, 1, 16, 11008, 4096) == ("bf16_stream_32x128x64", 5)
+    assert q(BF, 0, 1, 16, 4096, 11008) == ("bf16_stream_32x128x64", 8)
+    assert q(BF, 0, 1, 128, 11008, 4096) == ("bf16_stream_128x128x64", 2)
+    assert q(BF, 0, 1, 64, 11008, 4096)[0] == "bf16_stream_64x128x64"
+    assert q(BF, 0, 1, 16, 11008, 4096, workspace_bytes=0) == ("bf16_stream_32x128x64", 1)   # no workspace, no split
+    # squares: <= 256 tiles of 128x128 three-stage kernel, 257..512 two-stage, beyond that 256x256
+    assert q(BF, 0, 0, 1024, 1024, 1024)[0] == "bf16_stream_128x128x64"
+    assert q(BF, 0, 0, 2048, 2048, 2048) == ("bf16_stream_128x128x64", 1)
+    assert q(BF, 0, 0, 2304, 2304, 2304) == ("bf16_128x128x64", 1)
+    assert q(BF, 0, 0, 2816, 2816, 2816) == ("bf16_128x128x64", 1)
+    assert q(BF, 0, 0, 3072, 3072, 3072) == ("bf16_pingpong_256x256x64", 1)
+    # batch-reduce into a small C: split over the flattened (batch, k) range
+    name, split = q(BF, 0, 0, 512, 512, 64, batch=64, lda=64, ldb=512)
+    assert name == "bf16_stream_128x128x64" and split == 8
+    # fp32: one kernel, split by the time model
+    assert q(F32, 0, 0, 2048, 2048, 2048) == ("f32_128x128x32", 1)
+    assert q(F32, 0, 0, 1024, 1024, 1024) == ("f32_128x128x32", 4)
+    assert q(F32, 0, 0, 256, 256, 256) == ("f32_128x128x32", 8)
+    # shapes the tuned kernels do not take run on the general kernel
+    assert q(BF, 0, 0, 257, 131, 67)[0].startswith("generic")
+    assert q(F32, 0, 0, 257, 131, 67)[0].startswith("generic")
+    assert q(BF, 0, 0, 256, 256, 256, lda=260)[0].startswith("generic")        # ld % 8 != 0
+    # bad queries
+    import ctypes
+    v, s = ctypes.c_int(), ctypes.c_int()
+    assert lib.gemm_query_plan(7, 0, 0, 4, 4, 4, 1, 4, 4, 0, ctypes.byref(v), ctypes.byref(s)) == B.INVALID_ARG
+    assert lib.gemm_query_plan(1, 0, 0, 4, 4, 64, 1, 8, 4, 0, ctypes.byref(v), ctypes.byref(s)) == B.INVALID_ARG
