@@ -329,3 +329,30 @@ int oracle_gemm_s8(int transA, int transB, int64_t M, int64_t N, int64_t K,
         }
     return 0;
 }
+
+/*
+ * FP8 operands (Section 5(c): further packed types follow the same structure; the 8-bit
+ * float of the OCP "E4M3" kind: 1 sign, 4 exponent bits with bias 7, 3 fraction bits, no
+ * infinities, the single NaN pattern S.1111.111, largest finite value 448).  Decoded on
+ * values, exactly; the product of the widened operands is then the oracle above with fp32
+ * inputs, since every E4M3 value is exactly representable in fp32.
+ */
+double oracle_f8e4m3_to_f64(uint8_t b)
+{
+    const int sign = b >> 7, e = (b >> 3) & 15, f = b & 7;
+    double v;
+    if (e == 15 && f == 7)
+        v = NAN;
+    else if (e == 0)
+        v = ldexp((double)f, -9);                    /* subnormal: f/8 * 2^-6 */
+    else
+        v = ldexp(1.0 + (double)f / 8.0, e - 7);
+    return sign ? -v : v;
+}
+
+/* Widen `count` E4M3 bytes to fp32 (exact). */
+void oracle_f8e4m3_widen(const uint8_t *src, int64_t count, float *dst)
+{
+    for (int64_t i = 0; i < count; ++i)
+        dst[i] = (float)oracle_f8e4m3_to_f64(src[i]);
+}

@@ -50,6 +50,10 @@ def _load():
     lib.oracle_f16_to_f64.argtypes = [ctypes.c_uint16]
     lib.oracle_num_threads.restype = cint
     lib.oracle_num_threads.argtypes = []
+    lib.oracle_f8e4m3_to_f64.restype = ctypes.c_double
+    lib.oracle_f8e4m3_to_f64.argtypes = [ctypes.c_uint8]
+    lib.oracle_f8e4m3_widen.restype = None
+    lib.oracle_f8e4m3_widen.argtypes = [vp, i64, vp]
     lib.oracle_gemm_s8.restype = cint
     lib.oracle_gemm_s8.argtypes = [cint, cint, i64, i64, i64, vp, i64, vp, i64, cint, vp, i64, vp]
     lib.oracle_pack_vnni.restype = cint
@@ -205,4 +209,17 @@ def gemm_s8_ref(A, lda, B, ldb, M, N, K, *, transA=0, transB=0, C0=None, ldc0=No
                                 _ptr(C0) if acc else ctypes.c_void_p(0), int(ldc0 or 0), _ptr(out))
     if rc != 0:
         raise ValueError("oracle_gemm_s8 rejected its arguments")
+    return out
+
+
+def f8e4m3_to_f64(byte):
+    """Exact value of one FP8 E4M3 pattern."""
+    return float(_load().oracle_f8e4m3_to_f64(int(byte)))
+
+
+def f8e4m3_widen(a):
+    """uint8 array of E4M3 patterns -> float32 array of the same shape (exact)."""
+    a = np.ascontiguousarray(a, dtype=np.uint8)
+    out = np.empty(a.shape, dtype=np.float32)
+    _load().oracle_f8e4m3_widen(_ptr(a), a.size, _ptr(out))
     return out

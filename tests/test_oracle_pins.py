@@ -563,3 +563,35 @@ def test_s8_literal_extremes_and_library(oracle):
     # identity
     I = np.eye(K, dtype=np.int8)
     assert (oracle.gemm_s8_ref(Al, K, I, K, M, K, K) == Al).all()
+
+
+# ---------------------------------------------------------------- FP8 E4M3 decoder
+
+def test_f8e4m3_decoder_hand_values_and_structure(oracle):
+    d = oracle.f8e4m3_to_f64
+    assert d(0x00) == 0.0 and d(0x80) == 0.0 and np.signbit(d(0x80))
+    assert d(0x01) == 2.0 ** -9 and d(0x07) == 7 * 2.0 ** -9          # subnormals
+    assert d(0x08) == 2.0 ** -6                                      # smallest normal
+    assert d(0x38) == 1.0 and d(0x3C) == 1.5 and d(0xB8) == -1.0
+    assert d(0x40) == 2.0 and d(0x44) == 3.0 and d(0x48) == 4.0
+    assert d(0x7E) == 448.0 and d(0xFE) == -448.0                    # largest finite: no infinities
+    assert d(0x78) == 256.0                                          # exponent 15 is an ordinary binade
+    assert np.isnan(d(0x7F)) and np.isnan(d(0xFF))
+    vals = [d(b) for b in range(0x7F)]
+    assert all(x < y for x, y in zip(vals, vals[1:]))               # strictly increasing over the positive codes
+    for b in range(0x7F):
+        assert d(b | 0x80) == -d(b)
+    # every value is an integer multiple of 2^-9 and exactly representable in fp32
+    w = oracle.f8e4m3_widen(np.arange(256, dtype=np.uint8))
+    for b in range(256):
+        v = d(b)
+        if not np.isnan(v):
+            assert w[b] == v and (v * 512) == int(v * 512)
+    # second opinion where the library has the type
+    try:
+        import torch
+        t = torch.arange(256, dtype=torch.uint8).view(torch.float8_e4m3fn).to(torch.float32).numpy()
+        ok = ~np.isnan(t)
+        assert (t[ok] == w[ok]).all() and (np.isnan(t) == np.isnan(w)).all()
+    except (ImportError, AttributeError, RuntimeError):
+        pass
