@@ -107,6 +107,21 @@ int gemm_f16(int transA, int transB, int64_t M, int64_t N, int64_t K,
              void *workspace, size_t workspace_bytes, void *stream);
 
 /*
+ * FP8 GEMM (Section 5(c): further packed types follow the same structure).  A, B:
+ * device, one byte per element in the OCP E4M3 format (1 sign, 4 exponent bits with
+ * bias 7, 3 fraction bits; no infinities, NaN = S.1111.111, largest value 448);
+ * products are exact, sums are fp32; C is fp32 if c_is_f32 != 0, else bf16 (one
+ * rounding to nearest-even on store).  Layout and alignment rules of the
+ * matrix-instruction kernels as for gemm_s8 ("NT", K a multiple of 128, 16-byte
+ * aligned, leading dimensions multiples of 16); anything else runs on the general
+ * kernel with identical results up to the order of the fp32 summation.
+ */
+int gemm_f8(int transA, int transB, int64_t M, int64_t N, int64_t K,
+            const uint8_t *A, int64_t lda, const uint8_t *B, int64_t ldb,
+            float beta, void *C, int64_t ldc, int c_is_f32,
+            void *workspace, size_t workspace_bytes, void *stream);
+
+/*
  * int8 GEMM with exact int32 accumulation (Section 2.2 names INT8 among the packed
  * types; Section 5(c)):  C[M,N] = (accumulate ? C : 0) + A[M,K] x B[K,N].
  * A, B: device, signed 8-bit; C: device, int32; lda/ldb/ldc in elements.  Sums wrap

@@ -254,8 +254,8 @@ hipError_t launch_bf16_128x128(const Problem &p) { return launch_tile<128, 128>(
 // Alignment and shape rules of the kernels in this file.
 bool bf16_mfma_eligible(const Problem &p)
 {
-    if (p.in_s8) {
-        // int8: both operands k-contiguous, whole 128-byte k-rows, 16-byte aligned rows
+    if (in_8bit(p)) {
+        // one-byte elements: both operands k-contiguous, whole 128-byte k-rows, 16-byte aligned rows
         return p.transA == 0 && p.transB == 1 && p.batch == 1 && !p.A_off && !p.B_off && p.nmat == 1 &&
                p.K % 128 == 0 && !((uintptr_t)p.A & 15) && !((uintptr_t)p.B & 15) && !(p.lda & 15) &&
                !(p.ldb & 15) && p.lda < (1 << 23) && p.ldb < (1 << 23) && p.K / 128 < ((int64_t)1 << 31) &&

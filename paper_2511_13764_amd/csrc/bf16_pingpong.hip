@@ -175,10 +175,16 @@ __device__ __forceinline__ void pp_body(const Bf16Args &p)
             static_for<0, 3>([&](auto ic) {
                 constexpr int id = 3 * j + decltype(ic)::value;
                 constexpr int st = id / (PP_TM + PP_TN), q = id % (PP_TM + PP_TN);
-                if constexpr (q < PP_TM)
+                if constexpr (KIND == KIND_F8) {        // st = which half of the 32-byte operand
+                    if constexpr (q < PP_TM)
+                        fa[st][q] = ATile::read_frag16_f8(at, wm * PP_WM, q, st, lane);
+                    else
+                        fb[st][q - PP_TM] = BTile::read_frag16_f8(bt, wn * PP_WN, q - PP_TM, st, lane);
+                } else if constexpr (q < PP_TM) {
                     fa[st][q] = ATile::read_frag16(at, wm * PP_WM, q, st, lane);
-                else
+                } else {
                     fb[st][q - PP_TM] = BTile::read_frag16(bt, wn * PP_WN, q - PP_TM, st, lane);
+                }
             });
             if (request)
                 issue_one(j);
@@ -194,6 +200,15 @@ __device__ __forceinline__ void pp_body(const Bf16Args &p)
     // (B fragment first) so the 16x16 result is C^T: lane l owns row m = l%16 and the 4
     // consecutive columns 4*(l/16) .. +3.
     auto compute_block = [&]() {
+        if constexpr (KIND == KIND_F8) {
+            // one 128-deep instruction per accumulator: 32 MFMAs, the same pipe time
+#pragma unroll
+            for (int a = 0; a < PP_TN; ++a)
+#pragma unroll
+                for (int b = 0; b < PP_TM; ++b)
+                    acc[a][b] = mfma_16x16x128_f8(fb[0][a], fb[1][a], fa[0][b], fa[1][b], acc[a][b]);
+            return;
+        }
 #pragma unroll
         for (int st = 0; st < 2; ++st)
 #pragma unroll
@@ -379,9 +394,10 @@ static hipError_t launch_pp(const Problem &p)
     else if (lay == LAY_MN) kern = bf16_pingpong_kernel<false, LAY_MN, KIND>;          \
     else kern = bf16_pingpong_kernel<false, LAY_PACKED, KIND>;
     if (p.in_s8) kern = bf16_pingpong_kernel<true, LAY_K, KIND_S8>;
+    else if (p.in_f8) kern = bf16_pingpong_kernel<true, LAY_K, KIND_F8>;
     else if (p.in_f16) { BRG_PICK(KIND_F16) } else { BRG_PICK(KIND_BF16) }
 #undef BRG_PICK
-    static thread_local const void *configured[13] = {nullptr};
+    static thread_local const void *configured[14] = {nullptr};
     bool done = false;
     for (const void *c : configured)
         done = done || c == (const void *)kern;

@@ -169,12 +169,27 @@ bf16_stream_kernel(Bf16Args p)
 #pragma unroll
         for (int st = 0; st < 2; ++st) {
 #pragma unroll
-            for (int i = 0; i < TM; ++i)
-                fa[st][i] = ATile::read_frag16(at, wm * WM, i, st, lane);
+            for (int i = 0; i < TM; ++i) {
+                if constexpr (KIND == KIND_F8)
+                    fa[st][i] = ATile::read_frag16_f8(at, wm * WM, i, st, lane);
+                else
+                    fa[st][i] = ATile::read_frag16(at, wm * WM, i, st, lane);
+            }
 #pragma unroll
-            for (int i = 0; i < TN; ++i)
-                fb[st][i] = BTile::read_frag16(bt, wn * WN, i, st, lane);
+            for (int i = 0; i < TN; ++i) {
+                if constexpr (KIND == KIND_F8)
+                    fb[st][i] = BTile::read_frag16_f8(bt, wn * WN, i, st, lane);
+                else
+                    fb[st][i] = BTile::read_frag16(bt, wn * WN, i, st, lane);
+            }
         }
+        if constexpr (KIND == KIND_F8) {
+#pragma unroll
+            for (int a = 0; a < TN; ++a)
+#pragma unroll
+                for (int b = 0; b < TM; ++b)
+                    acc[a][b] = mfma_16x16x128_f8(fb[0][a], fb[1][a], fa[0][b], fa[1][b], acc[a][b]);
+        } else
 #pragma unroll
         for (int st = 0; st < 2; ++st)
 #pragma unroll
@@ -206,6 +221,8 @@ hipError_t launch_stream(const Problem &p)
            : p.transB == 1 ? bf16_stream_kernel<BM, AK, LAY_K, KIND> : bf16_stream_kernel<BM, AK, LAY_MN, KIND>;
     if (p.in_s8) {
         kern = bf16_stream_kernel<BM, true, LAY_K, KIND_S8>;
+    } else if (p.in_f8) {
+        kern = bf16_stream_kernel<BM, true, LAY_K, KIND_F8>;
     } else if (p.transA == 0) {
         if (p.in_f16) { BRG_PICK(true, KIND_F16) } else { BRG_PICK(true, KIND_BF16) }
     } else {
@@ -216,7 +233,7 @@ hipError_t launch_stream(const Problem &p)
         }
     }
 #undef BRG_PICK
-    static thread_local const void *configured[13] = {nullptr};
+    static thread_local const void *configured[14] = {nullptr};
     bool done = false;
     for (const void *c : configured)
         done = done || c == (const void *)kern;

@@ -45,6 +45,18 @@ __device__ __forceinline__ f32x16 mfma_32x32x16(bf16x8 a, bf16x8 b, f32x16 c)
         return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
 }
 
+typedef __attribute__((ext_vector_type(8))) int i32x8;
+
+// FP8 (E4M3 x E4M3): v_mfma_f32_16x16x128_f8f6f4 contracts 128 k per instruction, 32
+// bytes per lane and operand, given here as the two 16-byte chunks a lane read.  Which
+// k-bytes sit where inside the 32 is irrelevant as long as both operands agree.
+__device__ __forceinline__ f32x4 mfma_16x16x128_f8(bf16x8 a_lo, bf16x8 a_hi, bf16x8 b_lo, bf16x8 b_hi, f32x4 c)
+{
+    const i32x8 a = __builtin_shufflevector(__builtin_bit_cast(i32x4, a_lo), __builtin_bit_cast(i32x4, a_hi), 0, 1, 2, 3, 4, 5, 6, 7);
+    const i32x8 b = __builtin_shufflevector(__builtin_bit_cast(i32x4, b_lo), __builtin_bit_cast(i32x4, b_hi), 0, 1, 2, 3, 4, 5, 6, 7);
+    return __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(a, b, c, 0, 0, 0, 0, 0, 0);
+}
+
 #define LDS_AS __attribute__((address_space(3)))
 #define GLB_AS __attribute__((address_space(1)))
 
@@ -77,9 +89,10 @@ __device__ __forceinline__ void select_matrix(Bf16Args &p)
 // Host side: fill the fields every bf16 launcher shares.
 inline void fill_common_args(Bf16Args &a, const Problem &p)
 {
-    // The kernels address their operands in 2-byte units along k; an int8 problem (both
-    // operands k-contiguous) is handed over with K and the leading dimensions halved.
-    const int64_t u = p.in_s8 ? 2 : 1;
+    // The kernels address their operands in 2-byte units along k; a problem with
+    // one-byte elements (both operands k-contiguous) is handed over with K and the leading
+    // dimensions halved.
+    const int64_t u = in_8bit(p) ? 2 : 1;
     a.M = p.M; a.N = p.N; a.K = p.K / u; a.batch = p.batch;
     a.A = (const uint16_t *)p.A; a.A_off = p.A_off; a.lda = p.lda / u;
     a.B = (const uint16_t *)p.B; a.B_off = p.B_off; a.ldb = p.ldb / u;
@@ -213,6 +226,14 @@ struct KMajorTile {
     {
         const int r = row_base + t * 16 + (lane & 15);
         const int c = 4 * s + (lane >> 4);
+        return *(LDS_AS bf16x8 *)(tile + (uint32_t)(r * 128 + ((c ^ ((r >> 1) & 7)) << 4)));
+    }
+    // Half h (0 / 1) of the 32-byte operand of the 128-deep FP8 instruction: chunk
+    // 2 * (l/16) + h of the same row, so a lane's two halves are 32 consecutive k-bytes.
+    __device__ static bf16x8 read_frag16_f8(LDS_AS char *tile, int row_base, int t, int h, int lane)
+    {
+        const int r = row_base + t * 16 + (lane & 15);
+        const int c = 2 * (lane >> 4) + h;
         return *(LDS_AS bf16x8 *)(tile + (uint32_t)(r * 128 + ((c ^ ((r >> 1) & 7)) << 4)));
     }
 };

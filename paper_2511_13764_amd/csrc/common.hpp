@@ -12,7 +12,8 @@ namespace brg {
 struct Problem {
     int in_bf16;            // 1: A, B are bf16 bit patterns
     int in_f16;             // 1: A, B are IEEE binary16 bit patterns
-    int in_s8;              // 1: A, B are signed 8-bit integers, C is int32 (all three 0: fp32)
+    int in_s8;              // 1: A, B are signed 8-bit integers, C is int32
+    int in_f8;              // 1: A, B are FP8 E4M3 patterns (all four 0: fp32)
     int transA, transB;     // 1: stored transposed (K x M / N x K), row-major
     int64_t M, N, K, batch;
     const void *A;          // base of every A_i
@@ -84,6 +85,19 @@ __device__ __forceinline__ uint32_t pack_f16x2(float lo, float hi)
 {
     return (uint32_t)f32_to_f16_rne(lo) | ((uint32_t)f32_to_f16_rne(hi) << 16);
 }
+// FP8 E4M3 (OCP: bias 7, no infinities, NaN = S.1111.111) widened exactly.
+__device__ __forceinline__ float f8e4m3_to_f32(uint8_t b)
+{
+    const int e = (b >> 3) & 15, f = b & 7;
+    float v;
+    if (e == 15 && f == 7)
+        v = __uint_as_float(0x7fc00000u);
+    else if (e == 0)
+        v = (float)f * 0.001953125f;                         // f * 2^-9
+    else
+        v = __uint_as_float((uint32_t)(e + 120) << 23 | (uint32_t)f << 20);     // (1 + f/8) * 2^(e-7)
+    return (b & 0x80) ? -v : v;
+}
 // 16-bit C element of either kind.
 __device__ __forceinline__ float c16_to_f32(uint16_t h, int f16) { return f16 ? f16_to_f32(h) : bf16_to_f32(h); }
 __device__ __forceinline__ uint32_t pack_c16x2(float lo, float hi, int f16)
@@ -139,8 +153,8 @@ __device__ __forceinline__ void epilogue_store(const Epilogue &e, float v, int64
 
 inline bool in_16bit(const Problem &p) { return p.in_bf16 || p.in_f16; }
 // Operand kinds as template arguments of the kernels that move 128-byte k-rows.
-constexpr int KIND_BF16 = 0, KIND_F16 = 1, KIND_S8 = 2;
-inline int kind_of(const Problem &p) { return p.in_s8 ? KIND_S8 : p.in_f16 ? KIND_F16 : KIND_BF16; }
+constexpr int KIND_BF16 = 0, KIND_F16 = 1, KIND_S8 = 2, KIND_F8 = 3;
+inline bool in_8bit(const Problem &p) { return p.in_s8 || p.in_f8; }
 
 // ---- launchers (each returns the hipError_t of its launch) -------------------
 

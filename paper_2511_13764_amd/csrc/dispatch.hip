@@ -22,7 +22,7 @@ bool variant_eligible(int v, const Problem &p)
 {
     switch (v) {
     case V_GENERIC: return true;
-    case V_BF16_128x128: return bf16_mfma_eligible(p);
+    case V_BF16_128x128: return bf16_mfma_eligible(p) && !p.in_f8;      // no 32x32 FP8 form here
     case V_BF16_PP256: return bf16_pingpong_eligible(p);
     case V_F32_128x128: return f32_mfma_eligible(p);
     case V_BF16_STREAM32: return bf16_stream_eligible(p, 32);
@@ -142,7 +142,7 @@ int choose_plan(const Problem &p, size_t workspace_bytes, int forced_variant, in
             // Up to 256 tiles leave one workgroup per CU: the three-stage kernel hides the
             // load latency there (2048^3: 24.8 against 27.8 us); between 257 and 512 tiles
             // the two-stage kernel wins because two of its workgroups share a CU.
-            plan.variant = (t128 <= 256 && bf16_stream_eligible(p, 128)) ? V_BF16_STREAM128 : V_BF16_128x128;
+            plan.variant = ((t128 <= 256 || p.in_f8) && bf16_stream_eligible(p, 128)) ? V_BF16_STREAM128 : V_BF16_128x128;
             plan.split = single ? split_for_small_grid(p, workspace_bytes) : 1;
         }
     }

@@ -359,7 +359,7 @@ hipError_t launch_f32_128x128(const Problem &p)
 // its extent a multiple of 4 (whole 16-byte chunks).
 bool f32_mfma_eligible(const Problem &p)
 {
-    if (in_16bit(p) || p.in_s8 || !p.c_f32 || p.A_off || p.batch != 1)
+    if (in_16bit(p) || in_8bit(p) || !p.c_f32 || p.A_off || p.batch != 1)
         return false;
     if (p.K % FK != 0)
         return false;

@@ -19,7 +19,7 @@ constexpr int GT = 64;      // tile edge (M and N)
 constexpr int GK = 16;      // k-block
 constexpr int GPAD = 1;     // LDS row padding (floats)
 
-// KIND: 0 fp32, 1 bf16, 2 binary16
+// KIND: 0 fp32, 1 bf16, 2 binary16, 3 FP8 E4M3
 template <int KIND>
 __device__ __forceinline__ float load_in(const void *p, int64_t idx)
 {
@@ -27,6 +27,8 @@ __device__ __forceinline__ float load_in(const void *p, int64_t idx)
         return bf16_to_f32(((const uint16_t *)p)[idx]);
     if (KIND == 2)
         return f16_to_f32(((const uint16_t *)p)[idx]);
+    if (KIND == 3)
+        return f8e4m3_to_f32(((const uint8_t *)p)[idx]);
     return ((const float *)p)[idx];
 }
 
@@ -169,7 +171,7 @@ hipError_t launch_generic(const Problem &p)
 {
     dim3 grid((unsigned)((p.N + GT - 1) / GT), (unsigned)((p.M + GT - 1) / GT), (unsigned)p.split);
     // A batched call runs one launch per matrix here (this is the slow general path).
-    const int64_t esz = in_16bit(p) ? 2 : 4, csz = p.c_f32 ? 4 : 2;
+    const int64_t esz = p.in_f8 ? 1 : in_16bit(p) ? 2 : 4, csz = p.c_f32 ? 4 : 2;
     for (int64_t z = 0; z < p.nmat; ++z) {
         Epilogue e = make_epilogue(p);
         e.C = (char *)p.C + z * p.ms_c * csz;
@@ -179,6 +181,9 @@ hipError_t launch_generic(const Problem &p)
             hipLaunchKernelGGL(generic_kernel<1>, grid, dim3(256), 0, p.stream, p.transA,
                                p.b_packed ? 2 : p.transB, p.M, p.N, p.K, p.batch, A, p.A_off, p.lda, B, p.B_off,
                                p.ldb, e, p.split, p.partial);
+        else if (p.in_f8)
+            hipLaunchKernelGGL(generic_kernel<3>, grid, dim3(256), 0, p.stream, p.transA, p.transB, p.M, p.N,
+                               p.K, p.batch, A, p.A_off, p.lda, B, p.B_off, p.ldb, e, p.split, p.partial);
         else if (p.in_f16)
             hipLaunchKernelGGL(generic_kernel<2>, grid, dim3(256), 0, p.stream, p.transA, p.transB, p.M, p.N,
                                p.K, p.batch, A, p.A_off, p.lda, B, p.B_off, p.ldb, e, p.split, p.partial);

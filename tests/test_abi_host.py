@@ -218,3 +218,14 @@ def test_shape_to_tile_table(lib):
     v, s = ctypes.c_int(), ctypes.c_int()
     assert lib.gemm_query_plan(7, 0, 0, 4, 4, 4, 1, 4, 4, 0, ctypes.byref(v), ctypes.byref(s)) == B.INVALID_ARG
     assert lib.gemm_query_plan(1, 0, 0, 4, 4, 64, 1, 8, 4, 0, ctypes.byref(v), ctypes.byref(s)) == B.INVALID_ARG
+
+
+def test_f8_argument_rules(lib):
+    def call(**kw):
+        a = dict(tA=0, tB=1, M=4, N=8, K=128, A=P, lda=128, B=P, ldb=128, beta=0.0, C=P, ldc=8, f32=1)
+        a.update(kw)
+        return B.gemm_f8(a["tA"], a["tB"], a["M"], a["N"], a["K"], a["A"], a["lda"], a["B"], a["ldb"], a["beta"],
+                         a["C"], a["ldc"], a["f32"], stream=0, check=False)
+    assert call(M=0) == B.OK and call(N=0) == B.OK
+    for kw in (dict(M=-1), dict(K=-1), dict(tB=2), dict(lda=127), dict(ldb=127), dict(ldc=7), dict(B=0), dict(C=0)):
+        assert call(**kw) == B.INVALID_ARG, kw
