@@ -45,8 +45,8 @@ def main():
                     help="only run three plain 1 GiB device copies (reference for FETCH_SIZE / WRITE_SIZE counters)")
     args = ap.parse_args()
     if args.gpus != 1:
-        print("bench.py: this build runs on one GPU; --gpus must be 1 "
-              "(a multi-GPU job would shard M or N with no exchange, see DESIGN.md)", file=sys.stderr)
+        print("bench.py: the library runs on one GPU; --gpus must be 1 "
+              "(a multi-GPU job would shard M or N across GPUs with no exchange)", file=sys.stderr)
         sys.exit(2)
 
     import numpy as np
