@@ -444,3 +444,28 @@ def test_seeded_random_shape_sweep(oracle):
         tol = 1e-5 if c_f32 else (H.TOL_BF16 if M * N >= 4096 else 4e-3)
         assert H.rel_fro(got, ref) <= tol, (case.name, B.gemm_variant_name(B.gemm_last_variant()))
     assert len(seen) >= 5, seen
+
+
+@pytest.mark.gpu
+def test_operand_larger_than_4_gib(oracle):
+    """A spans more than 2^32 bytes (2,097,408 x 1024 bf16): rows on both sides of the 4 GiB
+    line are checked, so every row offset has to be formed in 64 bits.  A is generated on the
+    device (input generation only); the sampled rows are copied back for the oracle."""
+    M, N, K = (1 << 21) + 256, 128, 1024
+    g = torch.Generator(device="cuda").manual_seed(20251113)
+    A = torch.randn((M, K), device="cuda", generator=g, dtype=torch.float32).to(torch.bfloat16)
+    assert A.numel() * 2 > (1 << 32)
+    Bm = W.to_bf16_bits(W.normal_f32(73, 1, (N, K)))                 # stored N x K ("NT")
+    dB = H.dev(Bm)
+    dC = torch.full((M, N), float("nan"), device="cuda", dtype=torch.float32)
+    B.gemm_bf16(0, 1, M, N, K, A, K, dB, K, 0.0, dC, N, 1)
+    torch.cuda.synchronize()
+    used = B.gemm_variant_name(B.gemm_last_variant())
+    say(f"4 GiB operand -> {used}")
+    rows = [0, 1, 255, 256, M // 2 - 1, M // 2, (1 << 21) - 1, 1 << 21, (1 << 21) + 1, M - 257, M - 256, M - 1]
+    idx = torch.tensor(rows, device="cuda")
+    A_rows = A[idx].cpu().view(torch.int16).numpy().view(np.uint16)
+    got = dC[idx].cpu().numpy().astype(np.float64)
+    ref = oracle.gemm_ref(A_rows, K, Bm, K, len(rows), N, K, transB=1)
+    assert H.rel_fro(got, ref) <= 1e-5
+    assert torch.isfinite(dC).all().item(), "some row of C was never written"
