@@ -1,21 +1,24 @@
-// bf16 GEMM kernel for few rows of A (skinny M: the M = 16 / 128 shapes of an MLP
+// bf16 GEMM kernels for few rows of A (skinny M: the M = 16 / 128 shapes of an MLP
 // layer), where the time goes into streaming the B matrix from HBM once, not into the
 // matrix pipe - the regime the paper describes as bound by memory bandwidth
-// (Section 6, discussion of the flat-layout results).  Its 128-row form also serves
-// grids of at most 256 tiles of 128 x 128 (one workgroup per CU anyway), where the
-// third stage hides the load latency that the two-stage 4-wave kernel exposes.
+// (Section 6, discussion of the flat-layout results) - and for grids of at most 256
+// tiles of 128 x 128 (one workgroup per CU anyway: the 1024^3 and 2048^3 squares, the
+// batch-reduce tiles).
 //
-// A workgroup of 4 or 8 wavefronts owns a BM x 128 block of C (BM = 32, 64 or 128) and
-// walks its share of K in 64-deep blocks.  What matters here is how many bytes are
-// in flight per CU, so the LDS is a ring of three stages, each holding one k-block
-// of A and B: the loads for block t + 2 are requested while block t is multiplied,
-// and the small footprint (60 to 96 KiB) lets a second workgroup share the CU.
-// (Sweeps of 2 to 8 stages on the MLP shapes: three is best or within 3 % of the
-// best everywhere; deeper rings lose the second workgroup and gain nothing.)
-// Loads are global->LDS DMA (no register staging), counted per wave with vmcnt:
-// before block t is read a wave waits until only the loads of block t + 1 are
-// outstanding, then one workgroup barrier publishes the block and frees the slot
+// bf16_stream_kernel: a workgroup of 4 or 8 wavefronts owns a BM x 128 block of C
+// (BM = 32 or 64; 128 only for FP8) and walks its share of K in 64-deep blocks.  What
+// matters here is how many bytes are in flight per CU, so the LDS is a ring of three
+// stages, each holding one k-block of A and B: the loads for block t + 2 are requested
+// while block t is multiplied, and the small footprint (60 to 96 KiB) lets a second
+// workgroup share the CU.  (Sweeps of 2 to 8 stages on the MLP shapes: three is best
+// or within 3 % of the best everywhere; deeper rings lose the second workgroup and
+// gain nothing.)  Loads are global->LDS DMA (no register staging), counted per wave
+// with vmcnt: before block t is read a wave waits until only the loads of block t + 1
+// are outstanding, then one workgroup barrier publishes the block and frees the slot
 // read in the previous iteration.
+//
+// bf16_stream128_kernel: the 128-row tile, with loading and multiplying given to
+// different waves (described at the kernel).
 #include "bf16_tiles.hpp"
 
 namespace brg {
@@ -206,6 +209,240 @@ bf16_stream_kernel(Bf16Args p)
     store_wave_tile16<TM, TN>(p, acc, m0 + wm * WM + (lane & 15), n0 + wn * WN + 4 * (lane >> 4), (int)blockIdx.y);
 }
 
+// ---------------------------------------------------------------------------
+// 128 x 128 tile with the work divided by kind: four waves multiply, four waves load.
+//
+// What bounds a 128 x 128 x 64 block on one CU (cycles per block, measured with
+// work-skipping copies of the kernel above and with s_memtime around its steps):
+// the matrix pipe needs 512 per SIMD; eight waves reading the fragments of 64 x 32
+// accumulator tiles need 600-1100 (96 KiB of LDS reads, a SIMD takes its share at
+// about 32 B/clk); the 32 global->LDS wave-loads need about 780 (a CU pulls at
+// most ~42 B/clk from L2 with every CU pulling), and a wave is held at each of its
+// loads until the address unit has taken it.  In the kernel above all of that is
+// serial: every wave requests loads, reads fragments, then multiplies - 0.63 us per
+// block where the loads alone need 0.34.
+//
+// Here waves 0-3 (one per SIMD) own 64 x 64 accumulator tiles (64 KiB of fragment
+// reads per block) and never touch global memory inside the loop; waves 4-7 (the
+// second wave of every SIMD) only request loads, eight per block each, and wait
+// for them.  One workgroup barrier per block, B(t), publishes block t and frees
+// the slot of block t - 1, into which the loaders then request block t + STAGES - 1.
+// A multiplying wave reads the fragments of the first 32-deep half of block t
+// while the matrix pipe works on the second half of block t - 1, and those of the
+// second half while it works on the first, so the pipe only idles for the barrier.
+// ---------------------------------------------------------------------------
+#ifndef BRG_ST128_STAGES
+#define BRG_ST128_STAGES 4
+#endif
+constexpr int S128_STAGES = BRG_ST128_STAGES;
+
+constexpr int S128_EPI_LD = ST_BN + 4;           // floats per staged row (528 B: conflict-free 16-byte writes)
+
+// All 512 threads: the staged 128 x 128 fp32 tile, two rows per wave and instruction, to
+// C (beta, bias, ReLU, narrowing) or to this split's partial sums.
+__device__ __forceinline__ void stream128_store_tile(const Bf16Args &p, LDS_AS char *smem, int tid, int64_t m0, int64_t n0)
+{
+    LDS_AS float *stage = (LDS_AS float *)smem;
+    const bool to_partial = p.split > 1;
+    float *part = to_partial ? p.partial + (int64_t)blockIdx.y * p.M * p.N : nullptr;
+    const bool vec = to_partial ? ((p.N & 3) == 0) : ((p.epi.ldc & 3) == 0 && (((uintptr_t)p.epi.C) & 15) == 0);
+#pragma unroll 2
+    for (int i = 0; i < 8; ++i) {
+        const int idx = i * 512 + tid;
+        const int row = idx >> 5, c4 = idx & 31;
+        const f32x4 v = *(LDS_AS f32x4 *)(stage + row * S128_EPI_LD + c4 * 4);
+        const int64_t m = m0 + row, n = n0 + c4 * 4;
+        if (m < p.M && n < p.N) {
+            if (to_partial)
+                store4_partial(part + m * p.N + n, p.N - n, vec, v[0], v[1], v[2], v[3]);
+            else
+                store4_epilogue(p.epi, m, n, p.N - n, vec, v[0], v[1], v[2], v[3]);
+        }
+    }
+}
+
+template <bool A_KMAJ, int B_LAY, int KIND>
+__global__ void __launch_bounds__(512)
+bf16_stream128_kernel(Bf16Args p)
+{
+    constexpr int BM = 128, NL = 4;              // NL: loader waves
+    static_assert(KIND != KIND_F8, "the 128-deep FP8 instruction takes a whole k-block");
+    typedef typename TileOf<BM, NL, A_KMAJ ? LAY_K : LAY_MN>::type ATile;
+    typedef typename TileOf<ST_BN, NL, B_LAY>::type BTile;
+    constexpr int WM = 64, WN = 64, TM = WM / 16, TN = WN / 16;
+    constexpr uint32_t A_BYTES = BM * BK * 2, B_BYTES = ST_BN * BK * 2;
+    constexpr uint32_t STAGE = A_BYTES + B_BYTES;
+    constexpr int LA = ATile::kPerWave, LB = BTile::kPerWave, L = LA + LB;
+    constexpr int stages = S128_STAGES, ahead = stages - 1;
+    static_assert(L == 8 && (stages - 2) * L <= 63, "outstanding loads must fit vmcnt");
+
+    extern __shared__ __attribute__((aligned(1024))) char smem_generic[];
+    LDS_AS char *smem = (LDS_AS char *)smem_generic;
+    select_matrix(p);
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
+
+    int tm, tn;
+    tile_coords(blockIdx.x, p.tiles_m, p.tiles_n, tm, tn);
+    const int64_t m0 = (int64_t)tm * BM, n0 = (int64_t)tn * ST_BN;
+
+    const int kblocks = (int)(p.K / BK);
+    const int total = (int)p.batch * kblocks;
+    const int per = (total + p.split - 1) / p.split;
+    const int it_begin = (int)blockIdx.y * per;
+    const int it_end = (it_begin + per < total) ? it_begin + per : total;
+    const int n_iter = it_end > it_begin ? it_end - it_begin : 0;
+
+    // A tile offset that is not a multiple of 8 elements sends the loaders to
+    // register-staged 2-byte loads (same LDS image; they complete before their LDS
+    // stores, so the counted waits find nothing outstanding).
+    bool direct = true;
+    if (p.A_off) {
+        int ok = 1;
+        for (int i = tid; i < (int)p.batch; i += 512)
+            ok &= (((p.A_off[i] | p.B_off[i]) & 7) == 0);
+        direct = __syncthreads_and(ok) != 0;
+    }
+
+    if (w >= 4) {
+        // ---------------- loader waves ----------------
+        const int wl = w - 4;
+        // Rows / columns past the edge are redirected to a valid one (their products
+        // land in accumulator rows / columns that are never stored), so every wave
+        // issues exactly L loads per block and the vmcnt arithmetic holds.
+        uint32_t a_src[LA], b_src[LB];
+#pragma unroll
+        for (int j = 0; j < LA; ++j)
+            a_src[j] = ATile::src_rel_bytes(wl, j, lane, m0, p.M, p.lda);
+#pragma unroll
+        for (int j = 0; j < LB; ++j)
+            b_src[j] = BTile::src_rel_bytes(wl, j, lane, n0, p.N, p.ldb);
+        const int64_t b_kstep = BTile::kstep(p.ldb);
+        const int64_t a_kstep = ATile::kstep(p.lda);
+        const int64_t a_origin = ATile::origin(m0, p.lda), b_origin = BTile::origin(n0, p.ldb);
+        int ld_i = n_iter > 0 ? it_begin / kblocks : 0;
+        int ld_kb = n_iter > 0 ? it_begin - ld_i * kblocks : 0;
+        const uint16_t *ld_a = uniform_ptr(p.A + (p.A_off ? p.A_off[ld_i] : 0) + a_origin + ld_kb * a_kstep);
+        const uint16_t *ld_b = uniform_ptr(p.B + (p.B_off ? p.B_off[ld_i] : 0) + b_origin + ld_kb * b_kstep);
+        int ld_slot = 0;
+        auto issue_one = [&](const char *base, uint32_t src, uint32_t dst) {
+            if (direct) {
+                load16_to_lds_saddr(base, src, (uint32_t)(size_t)(smem + dst));
+            } else {
+                const uint16_t *h = (const uint16_t *)(base + src);
+                s16x8 v;
+#pragma unroll
+                for (int e = 0; e < 8; ++e)
+                    v[e] = (short)h[e];
+                *(LDS_AS s16x8 *)(smem + dst + lane * 16) = v;
+            }
+        };
+        auto issue_block = [&]() {
+            const uint32_t base = (uint32_t)ld_slot * STAGE;
+#pragma unroll
+            for (int j = 0; j < LB; ++j)
+                issue_one((const char *)ld_b, b_src[j], base + A_BYTES + BTile::dst_byte(wl, j));
+#pragma unroll
+            for (int j = 0; j < LA; ++j)
+                issue_one((const char *)ld_a, a_src[j], base + ATile::dst_byte(wl, j));
+            if (++ld_kb == kblocks) {
+                ld_kb = 0;
+                ++ld_i;
+                if (p.A_off && ld_i < (int)p.batch) {
+                    ld_a = uniform_ptr(p.A + p.A_off[ld_i] + a_origin);
+                    ld_b = uniform_ptr(p.B + p.B_off[ld_i] + b_origin);
+                }
+            } else {
+                ld_a += a_kstep;
+                ld_b += b_kstep;
+            }
+            ld_slot = ld_slot + 1 == stages ? 0 : ld_slot + 1;
+        };
+        for (int s = 0; s < ahead && s < n_iter; ++s)
+            issue_block();
+        for (int t = 0; t < n_iter; ++t) {
+            // Block t has landed once only the stages - 2 younger blocks are outstanding.
+            if (t + ahead - 1 < n_iter)
+                wait_vmcnt_le<(stages - 2) * L>();
+            else
+                wait_vmcnt0();                      // tail: fewer blocks than slots remain
+            wait_lgkmcnt0();                        // register-staged blocks: their LDS stores
+            block_sync();                           // B(t)
+            if (t + ahead < n_iter)
+                issue_block();                      // into the slot of block t - 1
+        }
+        block_sync();                               // E1
+        block_sync();                               // E2: the staged tile is complete
+        stream128_store_tile(p, smem, tid, m0, n0);
+        return;
+    }
+
+    // ---------------- multiplying waves ----------------
+    const int wm = w >> 1, wn = w & 1;
+    f32x4 acc[TN][TM];
+#pragma unroll
+    for (int a = 0; a < TN; ++a)
+#pragma unroll
+        for (int b = 0; b < TM; ++b)
+            acc[a][b] = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
+    bf16x8 fa[2][TM], fb[2][TN];
+    auto read_half = [&](LDS_AS char *at, LDS_AS char *bt, auto hc) {
+        constexpr int h = decltype(hc)::value;
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+            fa[h][i] = ATile::read_frag16(at, wm * WM, i, h, lane);
+#pragma unroll
+        for (int i = 0; i < TN; ++i)
+            fb[h][i] = BTile::read_frag16(bt, wn * WN, i, h, lane);
+    };
+    auto mfma_half = [&](auto hc) {
+        constexpr int h = decltype(hc)::value;
+#pragma unroll
+        for (int a = 0; a < TN; ++a)
+#pragma unroll
+            for (int b = 0; b < TM; ++b)
+                acc[a][b] = mfma_16x16x32<KIND>(fb[h][a], fa[h][b], acc[a][b]);
+    };
+    constexpr std::integral_constant<int, 0> H0{};
+    constexpr std::integral_constant<int, 1> H1{};
+    int rd_slot = 0;
+    for (int t = 0; t < n_iter; ++t) {
+        block_sync();                               // B(t): block t is in LDS
+        LDS_AS char *at = smem + (uint32_t)rd_slot * STAGE;
+        LDS_AS char *bt = at + A_BYTES;
+        read_half(at, bt, H0);
+        if (t > 0)
+            mfma_half(H1);                          // second half of block t - 1
+        __builtin_amdgcn_sched_barrier(0);
+        read_half(at, bt, H1);
+        mfma_half(H0);
+        __builtin_amdgcn_sched_barrier(0);
+        // Every read of block t is complete before the barrier that lets the loaders
+        // overwrite its slot.
+        wait_lgkmcnt0();
+        rd_slot = rd_slot + 1 == stages ? 0 : rd_slot + 1;
+    }
+    if (n_iter > 0)
+        mfma_half(H1);
+    // Epilogue through LDS: written from the MFMA layout (lane l: row l % 16, columns
+    // 4 * (l / 16) .. + 3 of each 16 x 16 tile), read back row-wise by all eight waves,
+    // so that every store instruction covers whole rows of the tile instead of sixteen
+    // 32-byte pieces (measured: 4 us of an 8 MiB C went into such stores).
+    block_sync();                                   // E1: nobody reads fragments any more
+    LDS_AS float *stage = (LDS_AS float *)smem;
+#pragma unroll
+    for (int a = 0; a < TN; ++a)
+#pragma unroll
+        for (int b = 0; b < TM; ++b)
+            *(LDS_AS f32x4 *)(stage + (wm * WM + 16 * b + (lane & 15)) * S128_EPI_LD + wn * WN + 16 * a + 4 * (lane >> 4)) =
+                acc[a][b];
+    wait_lgkmcnt0();
+    block_sync();                                   // E2
+    stream128_store_tile(p, smem, tid, m0, n0);
+}
+
 template <int BM>
 hipError_t launch_stream(const Problem &p)
 {
@@ -214,26 +451,44 @@ hipError_t launch_stream(const Problem &p)
     a.tiles_m = (int)((p.M + BM - 1) / BM);
     a.tiles_n = (int)((p.N + ST_BN - 1) / ST_BN);
     const dim3 grid((unsigned)(a.tiles_m * a.tiles_n), (unsigned)p.split, (unsigned)p.nmat);
-    const size_t lds = (size_t)ST_STAGES * (BM + ST_BN) * BK * 2;
     void (*kern)(Bf16Args) = nullptr;
-#define BRG_PICK(AK, KIND)                                                                    \
-    kern = p.b_packed ? bf16_stream_kernel<BM, AK, LAY_PACKED, KIND>                           \
-           : p.transB == 1 ? bf16_stream_kernel<BM, AK, LAY_K, KIND> : bf16_stream_kernel<BM, AK, LAY_MN, KIND>;
-    if (p.in_s8) {
-        kern = bf16_stream_kernel<BM, true, LAY_K, KIND_S8>;
-    } else if (p.in_f8) {
-        kern = bf16_stream_kernel<BM, true, LAY_K, KIND_F8>;
-    } else if (p.transA == 0) {
-        if (p.in_f16) { BRG_PICK(true, KIND_F16) } else { BRG_PICK(true, KIND_BF16) }
-    } else {
-        if constexpr (BM == 128) {
-            if (p.in_f16) { BRG_PICK(false, KIND_F16) } else { BRG_PICK(false, KIND_BF16) }
+    size_t lds = (size_t)ST_STAGES * (BM + ST_BN) * BK * 2;
+    if constexpr (BM == 128) {
+        // Everything but FP8 takes the loader / multiplier form of the 128-row tile.
+#define BRG_PICK128(AK, KIND)                                                                 \
+    kern = p.b_packed ? bf16_stream128_kernel<AK, LAY_PACKED, KIND>                            \
+           : p.transB == 1 ? bf16_stream128_kernel<AK, LAY_K, KIND> : bf16_stream128_kernel<AK, LAY_MN, KIND>;
+        if (p.in_f8) {
+            kern = bf16_stream_kernel<BM, true, LAY_K, KIND_F8>;
         } else {
-            return hipErrorInvalidValue;
+            lds = (size_t)S128_STAGES * (BM + ST_BN) * BK * 2;
+            if (p.in_s8) {
+                kern = bf16_stream128_kernel<true, LAY_K, KIND_S8>;
+            } else if (p.transA == 0) {
+                if (p.in_f16) { BRG_PICK128(true, KIND_F16) } else { BRG_PICK128(true, KIND_BF16) }
+            } else {
+                if (p.in_f16) { BRG_PICK128(false, KIND_F16) } else { BRG_PICK128(false, KIND_BF16) }
+            }
         }
-    }
+#undef BRG_PICK128
+    } else {
+#define BRG_PICK(KIND)                                                                        \
+    kern = p.b_packed ? bf16_stream_kernel<BM, true, LAY_PACKED, KIND>                         \
+           : p.transB == 1 ? bf16_stream_kernel<BM, true, LAY_K, KIND> : bf16_stream_kernel<BM, true, LAY_MN, KIND>;
+        if (p.transA != 0)
+            return hipErrorInvalidValue;            // the 32- and 64-row tiles need a k-contiguous A
+        if (p.in_s8) {
+            kern = bf16_stream_kernel<BM, true, LAY_K, KIND_S8>;
+        } else if (p.in_f8) {
+            kern = bf16_stream_kernel<BM, true, LAY_K, KIND_F8>;
+        } else if (p.in_f16) {
+            BRG_PICK(KIND_F16)
+        } else {
+            BRG_PICK(KIND_BF16)
+        }
 #undef BRG_PICK
-    static thread_local const void *configured[14] = {nullptr};
+    }
+    static thread_local const void *configured[16] = {nullptr};
     bool done = false;
     for (const void *c : configured)
         done = done || c == (const void *)kern;
