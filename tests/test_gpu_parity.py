@@ -291,6 +291,50 @@ def test_brgemm_small_scattered(oracle, tA, tB, M, N, K, batch):
     assert np.array_equal(out_s, out_s2), "split reduction must be deterministic"
 
 
+@pytest.mark.parametrize("tA,tB", [(0, 0), (0, 1), (1, 0), (1, 1)])
+@pytest.mark.parametrize("M,N,K,batch", [(128, 256, 64, 9), (32, 384, 128, 5), (256, 512, 128, 3)])
+def test_brgemm_tile_offsets_not_16_byte_aligned(oracle, tA, tB, M, N, K, batch):
+    """Tile offsets live in device memory, so the host cannot route on their alignment: every MFMA
+    kernel votes on them and falls back to 2-byte loads staged through registers.  Odd offsets,
+    every variant that takes the problem forced in turn, NaN around the tiles."""
+    rng = np.random.default_rng(4321 + M + N + K + batch + 2 * tA + tB)
+    lda = (M if tA else K) + 8
+    ldb = (K if tB else N) + 8
+    a_rows, b_rows = (K if tA else M), (N if tB else K)
+    a_sz, b_sz = a_rows * lda, b_rows * ldb
+    slot = ((max(a_sz, b_sz) + 63) // 64 + 2) * 64
+    pool = np.full(slot * 2 * batch + 64, W.BF16_NAN, np.uint16)
+    order = rng.permutation(2 * batch)
+    jitter = rng.integers(1, 8, size=2 * batch) | 1            # odd: not even 4-byte aligned
+    A_off = order[:batch].astype(np.int64) * slot + 32 + jitter[:batch]
+    B_off = order[batch:].astype(np.int64) * slot + 32 + jitter[batch:]
+    for i in range(batch):
+        a = np.full((a_rows, lda), W.BF16_NAN, np.uint16)
+        b = np.full((b_rows, ldb), W.BF16_NAN, np.uint16)
+        a[:, :lda - 8] = W.normal_bf16(67, i, (a_rows, lda - 8))
+        b[:, :ldb - 8] = W.normal_bf16(67, 100 + i, (b_rows, ldb - 8))
+        pool[A_off[i]:A_off[i] + a_sz] = a.ravel()
+        pool[B_off[i]:B_off[i] + b_sz] = b.ravel()
+    C0 = W.normal_f32(67, 999, (M, N))
+    case = W.BrgemmCase(f"brgemm_oddoff_{M}x{N}x{K}x{batch}_t{tA}{tB}", M, N, K, batch, tA, tB, 1.0,
+                        pool, A_off, B_off, lda, ldb, C0)
+    ref = H.oracle_brgemm_case(oracle, case)
+    ws = B.gemm_workspace_bytes(1, M, N, K, batch)
+    ran = []
+    for v, name in enumerate(B.variants()):
+        for split in (1, 2):
+            say(f"{case.name} variant={name} split={split}")
+            try:
+                out = H.run_brgemm_case(case, workspace_bytes=ws, force=(v, split))
+            except B.BrgemmError as e:
+                assert e.code == B.INVALID_ARG          # variant does not take this dtype / layout
+                continue
+            assert np.isfinite(out).all(), (name, split)
+            assert H.rel_fro(out, ref) <= H.TOL_BF16_F32OUT, (name, split)
+            ran.append(name)
+    assert any("stream" in n for n in ran) and any("pingpong" in n for n in ran) and "bf16_128x128x64" in ran
+
+
 def test_fused_bias_relu(oracle):
     M, N, K = 200, 328, 264
     for dtype, c_f32, tB in [("bf16", False, 1), ("bf16", True, 0), ("f32", True, 0)]:
