@@ -175,12 +175,8 @@ __device__ __forceinline__ void pp_body(const Bf16Args &p)
             static_for<0, 3>([&](auto ic) {
                 constexpr int id = 3 * j + decltype(ic)::value;
                 constexpr int st = id / (PP_TM + PP_TN), q = id % (PP_TM + PP_TN);
-                if constexpr (KIND == KIND_F8) {        // st = which half of the 32-byte operand
-                    if constexpr (q < PP_TM)
-                        fa[st][q] = ATile::read_frag16_f8(at, wm * PP_WM, q, st, lane);
-                    else
-                        fb[st][q - PP_TM] = BTile::read_frag16_f8(bt, wn * PP_WN, q - PP_TM, st, lane);
-                } else if constexpr (q < PP_TM) {
+                // (FP8: the two reads are the halves of a lane's 32-byte operand, see read_frag16)
+                if constexpr (q < PP_TM) {
                     fa[st][q] = ATile::read_frag16(at, wm * PP_WM, q, st, lane);
                 } else {
                     fb[st][q - PP_TM] = BTile::read_frag16(bt, wn * PP_WN, q - PP_TM, st, lane);

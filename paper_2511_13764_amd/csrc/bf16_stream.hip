@@ -172,19 +172,11 @@ bf16_stream_kernel(Bf16Args p)
 #pragma unroll
         for (int st = 0; st < 2; ++st) {
 #pragma unroll
-            for (int i = 0; i < TM; ++i) {
-                if constexpr (KIND == KIND_F8)
-                    fa[st][i] = ATile::read_frag16_f8(at, wm * WM, i, st, lane);
-                else
-                    fa[st][i] = ATile::read_frag16(at, wm * WM, i, st, lane);
-            }
+            for (int i = 0; i < TM; ++i)            // FP8: st = which half of a lane's 32-byte operand
+                fa[st][i] = ATile::read_frag16(at, wm * WM, i, st, lane);
 #pragma unroll
-            for (int i = 0; i < TN; ++i) {
-                if constexpr (KIND == KIND_F8)
-                    fb[st][i] = BTile::read_frag16_f8(bt, wn * WN, i, st, lane);
-                else
-                    fb[st][i] = BTile::read_frag16(bt, wn * WN, i, st, lane);
-            }
+            for (int i = 0; i < TN; ++i)
+                fb[st][i] = BTile::read_frag16(bt, wn * WN, i, st, lane);
         }
         if constexpr (KIND == KIND_F8) {
 #pragma unroll

@@ -221,19 +221,15 @@ struct KMajorTile {
         return *(LDS_AS bf16x8 *)(tile + frag_byte(row_base, t, ks, lane));
     }
     // Operand of v_mfma_f32_16x16x32_bf16 for 16-row tile t and 32-deep k-step s: lane l
-    // holds row t*16 + l%16 and the 8 k-values of chunk 4*s + l/16.
+    // holds row t*16 + l%16 and the 8 k-values of chunk 4*s + l/16.  The 128-deep FP8
+    // instruction takes 32 bytes per lane: reads s = 0 and s = 1 of the same tile, i.e.
+    // chunks l/16 and 4 + l/16 of the row (which k-bytes a lane holds is free as long as
+    // both operands agree; the adjacent pair 2*(l/16), 2*(l/16) + 1 costs about 4
+    // bank-conflict cycles per read with this swizzle, this pair none).
     __device__ static bf16x8 read_frag16(LDS_AS char *tile, int row_base, int t, int s, int lane)
     {
         const int r = row_base + t * 16 + (lane & 15);
         const int c = 4 * s + (lane >> 4);
-        return *(LDS_AS bf16x8 *)(tile + (uint32_t)(r * 128 + ((c ^ ((r >> 1) & 7)) << 4)));
-    }
-    // Half h (0 / 1) of the 32-byte operand of the 128-deep FP8 instruction: chunk
-    // 2 * (l/16) + h of the same row, so a lane's two halves are 32 consecutive k-bytes.
-    __device__ static bf16x8 read_frag16_f8(LDS_AS char *tile, int row_base, int t, int h, int lane)
-    {
-        const int r = row_base + t * 16 + (lane & 15);
-        const int c = 2 * (lane >> 4) + h;
         return *(LDS_AS bf16x8 *)(tile + (uint32_t)(r * 128 + ((c ^ ((r >> 1) & 7)) << 4)));
     }
 };
