@@ -96,6 +96,49 @@ static int split_for_stream(const Problem &p, int bm, size_t workspace_bytes)
     return best;
 }
 
+// Tile height and reduction split for a grid of at most 256 tiles of 128 x 128 (small
+// squares, batch-reduce into a small C): operands that sit in L2 / the Infinity Cache, so
+// what counts is how many CUs have work and what a k-block costs a workgroup.  Shorter
+// tiles put more workgroups on the chip (1024^3: 256 tiles of 32 x 128 take 9.3 us, 64
+// tiles of 128 x 128 take 12.4), as long as they still all run at once; two workgroups of
+// the 32- and 64-row kernels share a CU.  Time model in microseconds, constants from
+// sweeps over 512^3 ... 2048^3, 512 x 512 x 4096 and the scattered batch-reduce
+// configuration: a k-block costs a workgroup 0.20 / 0.29 / 0.42 us at 32 / 64 / 128 rows
+// (twice that when every block starts with a tile offset fetched from memory), a split
+// costs a second launch (4.5 us) plus writing and reading its partial tiles.
+static void plan_small_grid(const Problem &p, size_t workspace_bytes, bool may_split, int *bm_out, int *split_out)
+{
+    static const int heights[] = {128, 64, 32};
+    static const double block_us[] = {0.42, 0.29, 0.20};
+    const int64_t kblocks = p.batch * (p.K / 64);
+    double best_t = 1e30;
+    *bm_out = 128;
+    *split_out = 1;
+    for (int i = 0; i < 3; ++i) {
+        const int bm = heights[i];
+        if (!bf16_stream_eligible(p, bm) || (bm < 128 && p.in_f8))
+            continue;
+        const int64_t tiles = ((p.M + bm - 1) / bm) * ((p.N + 127) / 128) * p.nmat;
+        if (bm < 128 && tiles > 256)
+            continue;
+        const int64_t at_once = bm == 128 ? 256 : 512;
+        for (int s = 1; s <= (may_split ? kMaxSplit : 1); ++s) {
+            const int64_t per = (kblocks + s - 1) / s;
+            if (s > 1 && (per < 2 || split_bytes(p, s) > workspace_bytes))
+                continue;
+            const double rounds = (double)((tiles * s + at_once - 1) / at_once);
+            double t = rounds * (double)per * block_us[i] * (p.A_off ? 2.0 : 1.0);
+            if (s > 1)
+                t += 4.5 + (double)s * (double)p.M * (double)p.N * 4.0 / 4.0e6;
+            if (t < best_t * 0.97) {     // near ties: the taller tile, the smaller split
+                best_t = t;
+                *bm_out = bm;
+                *split_out = s;
+            }
+        }
+    }
+}
+
 // Reduction split for the fp32 kernel when its 128x128 tiles cannot fill the chip.
 // Time model in microseconds, fitted to split sweeps (256^3 ... 2048^3 and the skinny
 // MLP shape): one workgroup per CU works through a 128x128x32 k-block in ~2.0 us
@@ -139,11 +182,18 @@ int choose_plan(const Problem &p, size_t workspace_bytes, int forced_variant, in
         if (t128 > 512) {
             plan.variant = V_BF16_PP256;
         } else {
-            // Up to 256 tiles leave one workgroup per CU: the three-stage kernel hides the
-            // load latency there (2048^3: 24.8 against 27.8 us); between 257 and 512 tiles
-            // the two-stage kernel wins because two of its workgroups share a CU.
-            plan.variant = ((t128 <= 256 || p.in_f8) && bf16_stream_eligible(p, 128)) ? V_BF16_STREAM128 : V_BF16_128x128;
-            plan.split = single ? split_for_small_grid(p, workspace_bytes) : 1;
+            // Up to 256 tiles leave at most one workgroup per CU: a streaming kernel, its
+            // tile height by how many workgroups that puts on the chip; between 257 and 512
+            // tiles the two-stage kernel wins because two of its workgroups share a CU.
+            if (t128 <= 256 && bf16_stream_eligible(p, 128)) {
+                int bm = 128, split = 1;
+                plan_small_grid(p, workspace_bytes, single, &bm, &split);
+                plan.variant = bm == 32 ? V_BF16_STREAM32 : bm == 64 ? V_BF16_STREAM64 : V_BF16_STREAM128;
+                plan.split = split;
+            } else {
+                plan.variant = (p.in_f8 && bf16_stream_eligible(p, 128)) ? V_BF16_STREAM128 : V_BF16_128x128;
+                plan.split = single ? split_for_small_grid(p, workspace_bytes) : 1;
+            }
         }
     }
     if (f32_mfma_eligible(p)) {

@@ -196,15 +196,19 @@ def test_shape_to_tile_table(lib):
     assert q(BF, 0, 1, 128, 11008, 4096) == ("bf16_stream_128x128x64", 2)
     assert q(BF, 0, 1, 64, 11008, 4096)[0] == "bf16_stream_64x128x64"
     assert q(BF, 0, 1, 16, 11008, 4096, workspace_bytes=0) == ("bf16_stream_32x128x64", 1)   # no workspace, no split
-    # squares: <= 256 tiles of 128x128 three-stage kernel, 257..512 two-stage, beyond that 256x256
-    assert q(BF, 0, 0, 1024, 1024, 1024)[0] == "bf16_stream_128x128x64"
+    # squares: up to 256 tiles of 128x128 a streaming kernel, its tile height by how many
+    # workgroups that puts on the chip; 257..512 tiles the two-stage kernel; beyond that 256x256
+    assert q(BF, 0, 0, 512, 512, 512) == ("bf16_stream_32x128x64", 1)
+    assert q(BF, 0, 0, 1024, 1024, 1024) == ("bf16_stream_32x128x64", 1)
+    assert q(BF, 1, 0, 1024, 1024, 1024) == ("bf16_stream_128x128x64", 1)      # m-contiguous A: 128 rows only
+    assert q(BF, 0, 0, 1280, 1280, 1280) == ("bf16_stream_64x128x64", 1)
+    assert q(BF, 0, 0, 1536, 1536, 1536) == ("bf16_stream_128x128x64", 1)
     assert q(BF, 0, 0, 2048, 2048, 2048) == ("bf16_stream_128x128x64", 1)
     assert q(BF, 0, 0, 2304, 2304, 2304) == ("bf16_128x128x64", 1)
     assert q(BF, 0, 0, 2816, 2816, 2816) == ("bf16_128x128x64", 1)
     assert q(BF, 0, 0, 3072, 3072, 3072) == ("bf16_pingpong_256x256x64", 1)
     # batch-reduce into a small C: split over the flattened (batch, k) range
-    name, split = q(BF, 0, 0, 512, 512, 64, batch=64, lda=64, ldb=512)
-    assert name == "bf16_stream_128x128x64" and split == 8
+    assert q(BF, 0, 0, 512, 512, 64, batch=64, lda=64, ldb=512) == ("bf16_stream_32x128x64", 8)
     # fp32: one kernel, split by the time model
     assert q(F32, 0, 0, 2048, 2048, 2048) == ("f32_128x128x32", 1)
     assert q(F32, 0, 0, 1024, 1024, 1024) == ("f32_128x128x32", 4)
