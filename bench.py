@@ -26,9 +26,9 @@ PEAK_F32 = 157.3        # TFLOP/s, fp32 MFMA
 HBM_TBS = 8.0
 # Bytes beyond L2 per launch of the headline kernel, from rocprofv3 --pmc FETCH_SIZE and
 # WRITE_SIZE passes over this same command (profiles/bf16_pingpong_256x256x64_gemm4096_nn.md):
-# (98429.6 KiB x 2.0 + 32768.0 KiB x 1.0) x 1024; the factors are what the same counters
+# (98431.1 KiB x 2.0 + 32768.0 KiB x 1.0) x 1024; the factors are what the same counters
 # read for a plain 1 GiB copy.  Valid for the kernel the counters were taken on only.
-HEADLINE_TRAFFIC = {"bf16_pingpong_256x256x64": (98429.6 * 2.0 + 32768.0 * 1.0) * 1024.0}
+HEADLINE_TRAFFIC = {"bf16_pingpong_256x256x64": (98431.1 * 2.0 + 32768.0 * 1.0) * 1024.0}
 
 
 def main():
