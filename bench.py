@@ -133,7 +133,11 @@ def main():
     measured = {"bf16_normal_operands": round(mfma_rate(B.DTYPE_BF16, ops_n), 1),
                 "bf16_zero_operands": round(mfma_rate(B.DTYPE_BF16, torch.zeros_like(ops_n)), 1),
                 "f32_uniform_operands": round(mfma_rate(B.DTYPE_F32, torch.rand(6 * 64, device="cuda", generator=g) * 2 - 1), 1),
-                "unit": "TFLOP/s", "what": "register-only MFMA issue loop, 2 waves per SIMD on every CU"}
+                "s8_uniform_operands": round(mfma_rate(B.PROBE_S8, torch.randint(-128, 128, (12 * 64 * 16,), device="cuda",
+                                                                               dtype=torch.int8, generator=g)), 1),
+                "f8_normal_operands": round(mfma_rate(B.PROBE_F8, torch.randn(12 * 64 * 32, device="cuda", generator=g)
+                                                      .to(torch.float8_e4m3fn)), 1),
+                "unit": "TFLOP/s (int8: TOP/s)", "what": "register-only MFMA issue loop, 2 waves per SIMD on every CU"}
 
     out = {
         "metric": METRIC, "value": round(value, 2), "unit": "TFLOP/s", "n_gpus": 1,
@@ -223,6 +227,7 @@ def main():
         record("s8_4096_nt", 2.0 * 4096 ** 3,
                lambda: B.gemm_s8(0, 1, 4096, 4096, 4096, a, 4096, b, 4096, 0, c, 4096), 5033.2, steps=100)
         others["s8_4096_nt"]["unit"] = "TOP/s (tflops / frac_mfma_peak fields), against 5033.2 TOP/s int8 MFMA"
+        others["s8_4096_nt"]["frac_of_measured_mfma_rate"] = round(others["s8_4096_nt"]["tflops"] / measured["s8_uniform_operands"], 4)
         del a, b, c
         # FP8 (E4M3) operands, bf16 results (NT); peak 5.0 PFLOP/s dense fp8
         a = torch.randn((4096, 4096), device="cuda").to(torch.float8_e4m3fn)
@@ -231,6 +236,7 @@ def main():
         record("f8_4096_nt", 2.0 * 4096 ** 3,
                lambda: B.gemm_f8(0, 1, 4096, 4096, 4096, a, 4096, b, 4096, 0.0, c, 4096, 0, workspace=ws), 5033.2,
                steps=100)
+        others["f8_4096_nt"]["frac_of_measured_mfma_rate"] = round(others["f8_4096_nt"]["tflops"] / measured["f8_normal_operands"], 4)
         del a, b, c
         # MLP shapes, weights stored N x K
         # The skinny cases are bound by the stream of the 90 MB weight matrix, which fits

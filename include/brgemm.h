@@ -277,7 +277,14 @@ int gemm_last_split(void);
  * sink: device, blocks * 512 floats, receives each lane's accumulator sum.
  * flops (host, may be NULL): receives the number of floating-point operations
  * of the launch.  Returns BRGEMM_OK, BRGEMM_INVALID_ARG or BRGEMM_HIP_ERROR.
+ * dtype BRGEMM_PROBE_S8 / BRGEMM_PROBE_F8 (the one-byte operand types of Section
+ * 5(c)): `iters` x 32 independent 16x16 instructions per wavefront (int8: 16x16x64,
+ * FP8 E4M3: 16x16x128) on 12 x 64 lane values of 16 (int8) or 32 (FP8) bytes, the
+ * first eight blocks of 64 A fragments, the last four B fragments; `flops` then
+ * counts integer or FP8 multiply-add operations the same way.
  */
+#define BRGEMM_PROBE_S8 3
+#define BRGEMM_PROBE_F8 4
 int gemm_mfma_probe(int dtype, const void *operands, int64_t iters, int blocks, float *sink,
                     double *flops, void *stream);
 

@@ -74,22 +74,79 @@ probe_f32_kernel(const float *ops, int64_t iters, float *sink)
     sink[(size_t)blockIdx.x * 512 + threadIdx.x] = s;
 }
 
+typedef __attribute__((ext_vector_type(4))) int pi32x4;
+typedef __attribute__((ext_vector_type(8))) int pi32x8;
+typedef __attribute__((ext_vector_type(4))) float pf32x4;
+
+// One-byte operands in the register shape of one wave of the 256 x 256 kernel: 8 A and 4 B
+// fragments, 32 accumulators of 16x16, 32 independent MFMAs per iteration.  BYTES = 16:
+// v_mfma_i32_16x16x64_i8; BYTES = 32: v_mfma_f32_16x16x128_f8f6f4 on E4M3 operands.
+template <int BYTES>
+__global__ void __launch_bounds__(512)
+probe_byte_kernel(const uint8_t *ops, int64_t iters, float *sink)
+{
+    const int lane = threadIdx.x & 63;
+    pi32x4 lo[12], hi[12];
+#pragma unroll
+    for (int q = 0; q < 12; ++q) {
+        const uint8_t *src = ops + ((size_t)q * 64 + lane) * BYTES;
+        lo[q] = *(const pi32x4 *)src;
+        hi[q] = BYTES == 32 ? *(const pi32x4 *)(src + 16) : lo[q];
+    }
+    pi32x4 acc_i[32];
+    pf32x4 acc_f[32];
+#pragma unroll
+    for (int i = 0; i < 32; ++i) {
+        acc_i[i] = pi32x4{0, 0, 0, 0};
+        acc_f[i] = pf32x4{0.0f, 0.0f, 0.0f, 0.0f};
+    }
+    for (int64_t it = 0; it < iters; ++it) {
+#pragma unroll
+        for (int a = 0; a < 4; ++a)
+#pragma unroll
+            for (int b = 0; b < 8; ++b) {
+                if constexpr (BYTES == 16) {
+                    acc_i[a * 8 + b] = __builtin_amdgcn_mfma_i32_16x16x64_i8(lo[8 + a], lo[b], acc_i[a * 8 + b], 0, 0, 0);
+                } else {
+                    const pi32x8 fa = __builtin_shufflevector(lo[8 + a], hi[8 + a], 0, 1, 2, 3, 4, 5, 6, 7);
+                    const pi32x8 fb = __builtin_shufflevector(lo[b], hi[b], 0, 1, 2, 3, 4, 5, 6, 7);
+                    acc_f[a * 8 + b] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(fa, fb, acc_f[a * 8 + b], 0, 0, 0, 0, 0, 0);
+                }
+            }
+    }
+    float s = 0.0f;
+#pragma unroll
+    for (int i = 0; i < 32; ++i)
+#pragma unroll
+        for (int r = 0; r < 4; ++r)
+            s += BYTES == 16 ? (float)acc_i[i][r] : acc_f[i][r];
+    sink[(size_t)blockIdx.x * 512 + threadIdx.x] = s;
+}
+
 }  // namespace
 
 extern "C" int gemm_mfma_probe(int dtype, const void *operands, int64_t iters, int blocks, float *sink,
                                double *flops, void *stream)
 {
-    if ((dtype != BRGEMM_DTYPE_F32 && dtype != BRGEMM_DTYPE_BF16) || !operands || !sink || iters < 0 ||
-        blocks <= 0 || blocks > (1 << 20))
+    if ((dtype != BRGEMM_DTYPE_F32 && dtype != BRGEMM_DTYPE_BF16 && dtype != BRGEMM_PROBE_S8 && dtype != BRGEMM_PROBE_F8) ||
+        !operands || !sink || iters < 0 || blocks <= 0 || blocks > (1 << 20))
         return BRGEMM_INVALID_ARG;
-    const double per_mfma = dtype == BRGEMM_DTYPE_BF16 ? 2.0 * 32 * 32 * 16 : 2.0 * 32 * 32 * 2;
+    const bool bytes = dtype == BRGEMM_PROBE_S8 || dtype == BRGEMM_PROBE_F8;
+    const double per_mfma = dtype == BRGEMM_DTYPE_BF16 ? 2.0 * 32 * 32 * 16 : dtype == BRGEMM_DTYPE_F32 ? 2.0 * 32 * 32 * 2
+                            : dtype == BRGEMM_PROBE_S8 ? 2.0 * 16 * 16 * 64 : 2.0 * 16 * 16 * 128;
     if (flops)
-        *flops = per_mfma * 8.0 * (double)iters * 8.0 * (double)blocks;   // 8 MFMAs x 8 waves
+        *flops = per_mfma * (bytes ? 32.0 : 8.0) * (double)iters * 8.0 * (double)blocks;   // MFMAs per iteration x 8 waves
     if (dtype == BRGEMM_DTYPE_BF16)
         probe_bf16_kernel<<<dim3((unsigned)blocks), dim3(512), 0, (hipStream_t)stream>>>(
             (const uint16_t *)operands, iters, sink);
-    else
+    else if (dtype == BRGEMM_DTYPE_F32)
         probe_f32_kernel<<<dim3((unsigned)blocks), dim3(512), 0, (hipStream_t)stream>>>(
             (const float *)operands, iters, sink);
+    else if (dtype == BRGEMM_PROBE_S8)
+        probe_byte_kernel<16><<<dim3((unsigned)blocks), dim3(512), 0, (hipStream_t)stream>>>(
+            (const uint8_t *)operands, iters, sink);
+    else
+        probe_byte_kernel<32><<<dim3((unsigned)blocks), dim3(512), 0, (hipStream_t)stream>>>(
+            (const uint8_t *)operands, iters, sink);
     return hipGetLastError() == hipSuccess ? BRGEMM_OK : BRGEMM_HIP_ERROR;
 }

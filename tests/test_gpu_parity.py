@@ -384,7 +384,7 @@ def test_every_variant_on_an_aligned_problem(oracle):
 def test_mfma_probe_counts_what_it_claims():
     """The register-only issue loop really executes iters x 8 matrix instructions per
     wave: with all-ones operands every accumulator element grows by the reduction
-    depth (16 for bf16, 2 for fp32) per instruction."""
+    depth (16 for bf16, 2 for fp32, 64 for int8, 128 for FP8) per instruction."""
     iters, blocks = 37, 5
     sink = torch.empty(blocks * 512, dtype=torch.float32, device="cuda")
     ones_h = torch.ones(6 * 64 * 8, device="cuda").to(torch.bfloat16)
@@ -395,6 +395,15 @@ def test_mfma_probe_counts_what_it_claims():
     fl = B.gemm_mfma_probe(B.DTYPE_F32, ones_f, iters, blocks, sink)
     assert fl == 2.0 * 32 * 32 * 2 * 8 * iters * 8 * blocks
     assert (sink.cpu().numpy() == 8 * 16 * iters * 2).all()
+    # one-byte operands: 32 instructions of 16x16 per iteration, 4 accumulator elements per lane
+    ones_b = torch.ones(12 * 64 * 16, device="cuda", dtype=torch.int8)
+    fl = B.gemm_mfma_probe(B.PROBE_S8, ones_b, iters, blocks, sink)
+    assert fl == 2.0 * 16 * 16 * 64 * 32 * iters * 8 * blocks
+    assert (sink.cpu().numpy() == 32 * 4 * iters * 64).all()
+    ones_q = torch.full((12 * 64 * 32,), 0x38, device="cuda", dtype=torch.uint8)     # E4M3 1.0
+    fl = B.gemm_mfma_probe(B.PROBE_F8, ones_q, iters, blocks, sink)
+    assert fl == 2.0 * 16 * 16 * 128 * 32 * iters * 8 * blocks
+    assert (sink.cpu().numpy() == 32 * 4 * iters * 128).all()
 
 
 @pytest.mark.gpu
