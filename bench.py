@@ -203,6 +203,16 @@ def main():
         record("f32_2048_beta0.5", c2.flops,
                lambda: B.gemm_f32(0, 0, 2048, 2048, 2048, a2, 2048, b2, 2048, 0.5, c2d, 2048, workspace=ws), PEAK_F32)
         del a2, b2, c2d
+        # fp32 at the 4096^3 point of the metric (same distribution, device-generated: timing only)
+        a4 = torch.rand((4096, 4096), device="cuda") * 2 - 1
+        b4 = torch.rand((4096, 4096), device="cuda") * 2 - 1
+        c4 = torch.rand((4096, 4096), device="cuda") * 2 - 1
+        record("f32_4096_beta0.5", 2.0 * 4096 ** 3,
+               lambda: B.gemm_f32(0, 0, 4096, 4096, 4096, a4, 4096, b4, 4096, 0.5, c4, 4096, workspace=ws), PEAK_F32,
+               steps=20, warmup=5)
+        others["f32_4096_beta0.5"]["frac_of_measured_mfma_rate"] = round(
+            others["f32_4096_beta0.5"]["tflops"] / measured["f32_uniform_operands"], 4)
+        del a4, b4, c4
         # bf16 squares (random device data of the same distribution: timing only)
         for s in (1024, 2048, 8192):
             a = torch.randn((s, s), device="cuda").to(torch.bfloat16)

@@ -58,6 +58,21 @@ def test_config2_f32_2048_beta(oracle):
     assert err <= H.TOL_F32
 
 
+def test_f32_4096_sampled(oracle):
+    """fp32 at the size the metric names (4096^3, beta = 0.5), launched as the benchmark times
+    it; the oracle computes sampled complete rows (first / last / interior tiles, both halves
+    of every wave tile)."""
+    case = W.config2_f32_2048(size=4096)
+    say(case.name)
+    out, _ = H.run_gemm_case(case, workspace_bytes=B.gemm_workspace_bytes(0, case.M, case.N, case.K))
+    assert B.gemm_variant_name(B.gemm_last_variant()) == "f32_128x128x32"
+    rows = H.sample_rows(4096, 64, tile=128)
+    ref = H.oracle_gemm_case(oracle, case, rows=rows)
+    err = H.rel_fro(H.widen(out[rows]), ref)
+    say(f"{case.name} rows={len(rows)} rel_fro={err:.3e}")
+    assert err <= H.TOL_F32
+
+
 @pytest.mark.parametrize("size", [1024, 2048])
 def test_config3_bf16_square_full(oracle, size):
     case = W.config3_bf16_square(size)
