@@ -154,8 +154,27 @@ bf16_stream_kernel(Bf16Args p)
     for (int s = 0; s < ahead && s < n_iter; ++s)
         issue_loads();
 
+    // The MFMAs of the second 32-deep half of a block are issued at the top of the next
+    // iteration, so the matrix pipe works through the wait for the next block, the barrier
+    // and the load requests.  (Not for FP8: its 128-deep instruction needs both halves.)
+    bf16x8 fa[2][TM], fb[2][TN];
+    auto mfma_half = [&](auto hc) {
+        constexpr int h = decltype(hc)::value;
+#pragma unroll
+        for (int a = 0; a < TN; ++a)
+#pragma unroll
+            for (int b = 0; b < TM; ++b)
+                acc[a][b] = mfma_16x16x32<KIND == KIND_F8 ? KIND_BF16 : KIND>(fb[h][a], fa[h][b], acc[a][b]);
+    };
+    constexpr std::integral_constant<int, 0> H0{};
+    constexpr std::integral_constant<int, 1> H1{};
     int rd_slot = 0;
     for (int t = 0; t < n_iter; ++t) {
+        if constexpr (KIND != KIND_F8) {
+            if (t > 0)
+                mfma_half(H1);                      // second half of block t - 1
+            __builtin_amdgcn_sched_barrier(0);
+        }
         // Block t has landed once only the stages - 2 younger blocks are outstanding.
         if (t + stages - 2 < n_iter)
             wait_vmcnt_le<(ST_STAGES - 2) * L>();
@@ -168,7 +187,6 @@ bf16_stream_kernel(Bf16Args p)
             issue_loads();                          // into the slot read in iteration t - 1
         LDS_AS char *at = smem + (uint32_t)rd_slot * STAGE;
         LDS_AS char *bt = at + A_BYTES;
-        bf16x8 fa[2][TM], fb[2][TN];
 #pragma unroll
         for (int st = 0; st < 2; ++st) {
 #pragma unroll
@@ -184,18 +202,17 @@ bf16_stream_kernel(Bf16Args p)
 #pragma unroll
                 for (int b = 0; b < TM; ++b)
                     acc[a][b] = mfma_16x16x128_f8(fb[0][a], fb[1][a], fa[0][b], fa[1][b], acc[a][b]);
-        } else
-#pragma unroll
-        for (int st = 0; st < 2; ++st)
-#pragma unroll
-            for (int a = 0; a < TN; ++a)
-#pragma unroll
-                for (int b = 0; b < TM; ++b)
-                    acc[a][b] = mfma_16x16x32<KIND>(fb[st][a], fa[st][b], acc[a][b]);
+        } else {
+            mfma_half(H0);
+        }
         // The fragments are in registers before the next barrier lets another wave's
         // loads overwrite this slot.
         wait_lgkmcnt0();
         rd_slot = rd_slot + 1 == stages ? 0 : rd_slot + 1;
+    }
+    if constexpr (KIND != KIND_F8) {
+        if (n_iter > 0)
+            mfma_half(H1);
     }
 
     store_wave_tile16<TM, TN>(p, acc, m0 + wm * WM + (lane & 15), n0 + wn * WN + 4 * (lane >> 4), (int)blockIdx.y);
