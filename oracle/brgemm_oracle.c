@@ -223,6 +223,7 @@ int oracle_brgemm(int in_dtype, int transA, int transB,
         int64_t m = rows ? rows[r] : r;
         double *acc = ref + r * N;
         if (m < 0 || m >= M) {
+#pragma omp atomic write
             bad = 1;
             continue;
         }
