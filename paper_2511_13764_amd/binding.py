@@ -24,7 +24,7 @@ WORKSPACE_TOO_SMALL = -3
 HIP_ERROR = -4
 MISALIGNED_WORKSPACE = -5
 DTYPE_F32, DTYPE_BF16, DTYPE_F16 = 0, 1, 2
-PROBE_S8, PROBE_F8 = 3, 4
+PROBE_S8, PROBE_F8, PROBE_BF16_16X16X32 = 3, 4, 5
 EPI_NONE, EPI_BIAS, EPI_RELU = 0, 1, 2
 
 EXPORTS = ["gemm_f32", "gemm_bf16", "brgemm_bf16", "brgemm_fused", "gemm_workspace_bytes",

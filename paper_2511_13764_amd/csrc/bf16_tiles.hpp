@@ -469,8 +469,14 @@ __device__ __forceinline__ void store4_epilogue(const Epilogue &e, int64_t m, in
         }
     }
     if (e.bias) {
-        const f32x4 bv = *(const f32x4 *)(e.bias + n);     // n is a multiple of 4; bias from hipMalloc
-        v0 += bv[0]; v1 += bv[1]; v2 += bv[2]; v3 += bv[3];
+        // n is a multiple of 4, so the 16-byte read is aligned exactly when the bias
+        // pointer is; a bias that starts inside a larger buffer is read by element.
+        if ((((uintptr_t)e.bias) & 15) == 0) {
+            const f32x4 bv = *(const f32x4 *)(e.bias + n);
+            v0 += bv[0]; v1 += bv[1]; v2 += bv[2]; v3 += bv[3];
+        } else {
+            v0 += e.bias[n]; v1 += e.bias[n + 1]; v2 += e.bias[n + 2]; v3 += e.bias[n + 3];
+        }
     }
     if (e.relu) {
         v0 = v0 < 0.0f ? 0.0f : v0;

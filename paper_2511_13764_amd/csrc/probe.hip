@@ -11,8 +11,9 @@ namespace {
 typedef __attribute__((ext_vector_type(8))) __bf16 pbf16x8;
 typedef __attribute__((ext_vector_type(16))) float pf32x16;
 
-// Same register shape as one wave of the tuned bf16 kernel: 4 A fragments, 2 B
-// fragments, 8 accumulators of 32x32; 8 independent MFMAs per iteration.
+// Register shape of one wave of the 4-wave 128 x 128 kernel: 4 A fragments, 2 B
+// fragments, 8 accumulators of 32x32; 8 independent v_mfma_f32_32x32x16_bf16 per
+// iteration.
 __global__ void __launch_bounds__(512)
 probe_bf16_kernel(const uint16_t *ops, int64_t iters, float *sink)
 {
@@ -78,6 +79,38 @@ typedef __attribute__((ext_vector_type(4))) int pi32x4;
 typedef __attribute__((ext_vector_type(8))) int pi32x8;
 typedef __attribute__((ext_vector_type(4))) float pf32x4;
 
+// Register shape of one wave of the 256 x 256 ping-pong kernel and of the streaming
+// kernels: 8 A and 4 B fragments, 32 accumulators of 16x16, 32 independent
+// v_mfma_f32_16x16x32_bf16 per iteration (the same flop per pipe cycle as the 32x32x16
+// form; each accumulator register is read and written half as often per flop).
+__global__ void __launch_bounds__(512)
+probe_bf16_16x16_kernel(const uint16_t *ops, int64_t iters, float *sink)
+{
+    const int lane = threadIdx.x & 63;
+    pbf16x8 f[12];
+#pragma unroll
+    for (int q = 0; q < 12; ++q)
+        f[q] = *(const pbf16x8 *)(ops + ((size_t)q * 64 + lane) * 8);
+    pf32x4 acc[32];
+#pragma unroll
+    for (int i = 0; i < 32; ++i)
+        acc[i] = pf32x4{0.0f, 0.0f, 0.0f, 0.0f};
+    for (int64_t it = 0; it < iters; ++it) {
+#pragma unroll
+        for (int a = 0; a < 4; ++a)
+#pragma unroll
+            for (int b = 0; b < 8; ++b)
+                acc[a * 8 + b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(f[8 + a], f[b], acc[a * 8 + b], 0, 0, 0);
+    }
+    float s = 0.0f;
+#pragma unroll
+    for (int i = 0; i < 32; ++i)
+#pragma unroll
+        for (int r = 0; r < 4; ++r)
+            s += acc[i][r];
+    sink[(size_t)blockIdx.x * 512 + threadIdx.x] = s;
+}
+
 // One-byte operands in the register shape of one wave of the 256 x 256 kernel: 8 A and 4 B
 // fragments, 32 accumulators of 16x16, 32 independent MFMAs per iteration.  BYTES = 16:
 // v_mfma_i32_16x16x64_i8; BYTES = 32: v_mfma_f32_16x16x128_f8f6f4 on E4M3 operands.
@@ -128,15 +161,21 @@ probe_byte_kernel(const uint8_t *ops, int64_t iters, float *sink)
 extern "C" int gemm_mfma_probe(int dtype, const void *operands, int64_t iters, int blocks, float *sink,
                                double *flops, void *stream)
 {
-    if ((dtype != BRGEMM_DTYPE_F32 && dtype != BRGEMM_DTYPE_BF16 && dtype != BRGEMM_PROBE_S8 && dtype != BRGEMM_PROBE_F8) ||
+    if ((dtype != BRGEMM_DTYPE_F32 && dtype != BRGEMM_DTYPE_BF16 && dtype != BRGEMM_PROBE_S8 && dtype != BRGEMM_PROBE_F8 &&
+         dtype != BRGEMM_PROBE_BF16_16X16X32) ||
         !operands || !sink || iters < 0 || blocks <= 0 || blocks > (1 << 20))
         return BRGEMM_INVALID_ARG;
-    const bool bytes = dtype == BRGEMM_PROBE_S8 || dtype == BRGEMM_PROBE_F8;
+    // the 16x16 forms issue 32 instructions per iteration, the 32x32 forms 8
+    const bool small = dtype == BRGEMM_PROBE_S8 || dtype == BRGEMM_PROBE_F8 || dtype == BRGEMM_PROBE_BF16_16X16X32;
     const double per_mfma = dtype == BRGEMM_DTYPE_BF16 ? 2.0 * 32 * 32 * 16 : dtype == BRGEMM_DTYPE_F32 ? 2.0 * 32 * 32 * 2
-                            : dtype == BRGEMM_PROBE_S8 ? 2.0 * 16 * 16 * 64 : 2.0 * 16 * 16 * 128;
+                            : dtype == BRGEMM_PROBE_S8 ? 2.0 * 16 * 16 * 64
+                            : dtype == BRGEMM_PROBE_F8 ? 2.0 * 16 * 16 * 128 : 2.0 * 16 * 16 * 32;
     if (flops)
-        *flops = per_mfma * (bytes ? 32.0 : 8.0) * (double)iters * 8.0 * (double)blocks;   // MFMAs per iteration x 8 waves
-    if (dtype == BRGEMM_DTYPE_BF16)
+        *flops = per_mfma * (small ? 32.0 : 8.0) * (double)iters * 8.0 * (double)blocks;   // MFMAs per iteration x 8 waves
+    if (dtype == BRGEMM_PROBE_BF16_16X16X32)
+        probe_bf16_16x16_kernel<<<dim3((unsigned)blocks), dim3(512), 0, (hipStream_t)stream>>>(
+            (const uint16_t *)operands, iters, sink);
+    else if (dtype == BRGEMM_DTYPE_BF16)
         probe_bf16_kernel<<<dim3((unsigned)blocks), dim3(512), 0, (hipStream_t)stream>>>(
             (const uint16_t *)operands, iters, sink);
     else if (dtype == BRGEMM_DTYPE_F32)

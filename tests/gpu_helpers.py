@@ -59,8 +59,11 @@ def check_padding(out_full, N, c_is_f32):
         assert (pad == want).all(), "kernel wrote outside the N live columns of C"
 
 
-def run_gemm_case(case, *, ldc=None, workspace_bytes=0, bias=None, relu=False, force=None, via_fused=False):
-    """Run one GemmCase through the C ABI.  Returns (live output array, full buffer)."""
+def run_gemm_case(case, *, ldc=None, workspace_bytes=0, bias=None, relu=False, force=None, via_fused=False,
+                  bias_shift=0):
+    """Run one GemmCase through the C ABI.  Returns (live output array, full buffer).
+    bias_shift > 0 places the bias that many elements into a NaN-filled allocation, so
+    that its pointer is 4-byte but not 16-byte aligned."""
     M, N, K = case.M, case.N, case.K
     ldc = ldc or N
     c_is_f32 = case.c_is_f32
@@ -68,7 +71,11 @@ def run_gemm_case(case, *, ldc=None, workspace_bytes=0, bias=None, relu=False, f
     cbuf = make_c(M, N, ldc, c_is_f32, case.C0, case.beta)
     dC = dev(cbuf)
     ws = torch.empty(workspace_bytes, dtype=torch.uint8, device="cuda") if workspace_bytes else None
-    dbias = dev(bias) if bias is not None else None
+    dbias = None
+    if bias is not None:
+        holder = np.full(bias_shift + bias.size + 4, np.nan, np.float32)
+        holder[bias_shift:bias_shift + bias.size] = bias
+        dbias = dev(holder)[bias_shift:]
     if force is not None:
         B.gemm_force_variant(*force)
     try:
@@ -133,3 +140,38 @@ def sample_rows(M, count, tile=256, seed=5):
     fixed = [r for r in fixed if 0 <= r < M]
     extra = rng.integers(0, M, size=max(0, count - len(fixed))).tolist()
     return sorted(set(fixed + extra))
+
+
+def check_bf16_out_elementwise(oracle, out_bits, ref, abs_ref, K, *, what=""):
+    """Every element of a bf16 C against the fp64 oracle.
+
+    got = RNE_bf16(s), s an fp32 sum of the K exact products in some order.  abs_ref is
+    the oracle's product of the absolute values, i.e. S = sum_k |a_k b_k| per element.
+      (1) worst case: |s - ref| <= gamma_K * S  (gamma_K = K u / (1 - K u), u = 2^-24: the
+          textbook bound for any order of K - 1 fp32 additions), and the rounding to 8
+          significant bits moves s by at most half a spacing, 2^(floor(log2 |s|) - 8);
+          must hold for every element.
+      (2) the same with the rounding-error bound for errors that do not all pile up the
+          same way, 4 sqrt(K) u S (Higham & Mary's probabilistic gamma with lambda = 4),
+          about sqrt(K)/4 times tighter; also asserted for every element.  An element
+          whose sum lost or gained one term of typical size fails it.
+      (3) the stored bits equal the oracle's own rounding of ref except where the sum sits
+          within the fp32 error of a rounding boundary: at most 1 % of the elements.
+    Returns the largest |got - ref| / bound (2) and the fraction counted in (3)."""
+    u = 2.0 ** -24
+    got = widen(out_bits)
+    err = np.abs(got - ref)
+    tiny = 2.0 ** -133                                   # half the smallest bf16 subnormal
+    for name, delta in (("worst-case", (K * u / (1.0 - K * u)) * abs_ref),
+                        ("probabilistic", 4.0 * np.sqrt(K) * u * abs_ref)):
+        big = np.maximum(np.abs(ref) + delta, 2.0 ** -126)
+        bound = 2.0 ** (np.floor(np.log2(big)) - 8) + delta + tiny      # half a bf16 spacing at |s|
+        excess = err - bound
+        worst = np.unravel_index(np.argmax(excess), excess.shape)
+        assert excess[worst] <= 0.0, (f"{what}: element {worst} got {got[worst]} ref {ref[worst]} "
+                                      f"{name} bound {bound[worst]}")
+    ratio = float((err / bound).max())
+    want = oracle.round_to_out(ref, 1)
+    frac = float((out_bits != want).mean())
+    assert frac <= 0.01, f"{what}: {frac:.4f} of the elements differ from the oracle's rounding"
+    return ratio, frac

@@ -112,6 +112,32 @@ def test_config3_bf16_square_sampled(oracle, size):
     assert errc <= H.TOL_BF16
 
 
+def _abs_bits(x):
+    return x & np.uint16(0x7FFF)
+
+
+@pytest.mark.parametrize("which", ["square4096", "mlp_up4096"])
+def test_whole_c_elementwise_at_full_size(oracle, which):
+    """The benchmark's headline problem (bf16 4096^3 NN, bf16 out) and the M = 4096
+    up-projection (NT), launched as the benchmark launches them, with EVERY element of C
+    compared with the oracle: a per-element bound (one bf16 rounding plus the fp32
+    summation bound, see check_bf16_out_elementwise), at most one bf16 step from the
+    oracle's own rounding, and the Frobenius gate."""
+    case = W.config3_bf16_square(4096) if which == "square4096" else W.config4_mlp(4096, "up")
+    say(case.name)
+    ws = min(B.gemm_workspace_bytes(1, case.M, case.N, case.K), 1 << 30)
+    out, _ = H.run_gemm_case(case, workspace_bytes=ws)
+    assert B.gemm_variant_name(B.gemm_last_variant()) == "bf16_pingpong_256x256x64"
+    ref = H.oracle_gemm_case(oracle, case)
+    abs_ref = oracle.gemm_ref(_abs_bits(case.A), case.lda, _abs_bits(case.B), case.ldb, case.M, case.N, case.K,
+                              transA=case.transA, transB=case.transB)
+    err = H.rel_fro(H.widen(out), ref)
+    worst, frac = H.check_bf16_out_elementwise(oracle, out, ref, abs_ref, case.K, what=case.name)
+    say(f"{case.name} all {case.M * case.N} elements: rel_fro={err:.3e} worst |err|/bound={worst:.3f} "
+        f"differ from the oracle's rounding: {frac:.2e}")
+    assert err <= H.TOL_BF16
+
+
 @pytest.mark.parametrize("which", ["up", "down"])
 @pytest.mark.parametrize("M", [16, 128, 4096])
 def test_config4_mlp_shapes(oracle, which, M):
@@ -370,6 +396,75 @@ def test_fused_bias_relu(oracle):
         assert H.rel_fro(H.widen(out_b), ref_b) <= _tol(case)
 
 
+@pytest.mark.parametrize("dtype,c_f32", [("bf16", False), ("bf16", True), ("f32", True)])
+@pytest.mark.parametrize("tA,tB", [(0, 0), (0, 1), (1, 0)])
+def test_fused_epilogue_every_variant(oracle, dtype, c_f32, tA, tB):
+    """beta != 0, bias and ReLU (Section 6: the measured kernel is BRGEMM + bias + ReLU)
+    through the epilogue of every kernel variant that takes an aligned problem, with and
+    without a reduction split; the bias starts one element into its allocation."""
+    M, N, K = 512, 768, 512
+    Al = W.normal_f32(74, 0, (M, K))
+    Bl = W.normal_f32(74, 1, (K, N))
+    As = np.ascontiguousarray(Al.T if tA else Al)
+    Bs = np.ascontiguousarray(Bl.T if tB else Bl)
+    C0 = W.normal_f32(74, 2, (M, N), sigma=8.0)
+    bias = W.normal_f32(74, 3, (N,), sigma=8.0)
+    if dtype == "bf16":
+        As, Bs = W.to_bf16_bits(As), W.to_bf16_bits(Bs)
+    if not c_f32:
+        C0 = W.to_bf16_bits(C0)
+    case = W.GemmCase(f"epilogue_{dtype}_cf32{c_f32}_t{tA}{tB}", dtype, M, N, K, tA, tB, 0.75, As, Bs, C0, c_f32)
+    ref = H.oracle_gemm_case(oracle, case, bias=bias, relu=True)
+    ref_b = H.oracle_gemm_case(oracle, case, bias=bias, relu=False)
+    ws = B.gemm_workspace_bytes(1, M, N, K)
+    ran = []
+    for v, name in enumerate(B.variants()):
+        for split in (1, 2):
+            for shift in (0, 1):
+                say(f"{case.name} variant={name} split={split} bias_shift={shift}")
+                try:
+                    out, _ = H.run_gemm_case(case, workspace_bytes=ws, force=(v, split), bias=bias, relu=True,
+                                             bias_shift=shift)
+                except B.BrgemmError as e:
+                    assert e.code == B.INVALID_ARG          # variant does not take this dtype / layout
+                    continue
+                got = H.widen(out)
+                assert (got >= 0).all(), (name, split)
+                assert ((got == 0) == (ref <= 0)).mean() > 0.999, (name, split)
+                assert H.rel_fro(got, ref) <= _tol(case), (name, split, shift)
+                ran.append(name)
+            try:
+                out_b, _ = H.run_gemm_case(case, workspace_bytes=ws, force=(v, split), bias=bias, relu=False)
+            except B.BrgemmError:
+                continue
+            assert H.rel_fro(H.widen(out_b), ref_b) <= _tol(case), (name, split)
+    if dtype == "bf16":
+        want = {"bf16_pingpong_256x256x64", "bf16_128x128x64", "bf16_stream_128x128x64", "generic_64x64x16_f32mfma"}
+        if tA == 0:
+            want |= {"bf16_stream_32x128x64", "bf16_stream_64x128x64"}
+    else:
+        want = {"f32_128x128x32", "generic_64x64x16_f32mfma"}
+    assert want <= set(ran), set(ran)
+
+
+def test_mlp_up_4096_bias_relu(oracle):
+    """The paper's benchmark kernel at the up-projection shape: GEMM + bias + ReLU, bf16
+    out, NT, automatic plan (the 256 x 256 kernel's staged epilogue); sampled complete rows."""
+    case = W.config4_mlp(4096, "up")
+    bias = W.normal_f32(75, 3, (case.N,), sigma=2.0)
+    say(case.name + " + bias + relu")
+    out, _ = H.run_gemm_case(case, workspace_bytes=1 << 28, bias=bias, relu=True, bias_shift=3)
+    assert B.gemm_variant_name(B.gemm_last_variant()) == "bf16_pingpong_256x256x64"
+    rows = H.sample_rows(case.M, 64)
+    ref = H.oracle_gemm_case(oracle, case, rows=rows, bias=bias, relu=True)
+    got = H.widen(out[rows])
+    assert (H.widen(out) >= 0).all()
+    assert ((got == 0) == (ref <= 0)).mean() > 0.999
+    err = H.rel_fro(got, ref)
+    say(f"   rel_fro={err:.3e}")
+    assert err <= H.TOL_BF16
+
+
 def test_every_variant_on_an_aligned_problem(oracle):
     """Each kernel variant that accepts the problem, forced in turn, with and without a split."""
     M, N, K = 512, 768, 512
@@ -398,14 +493,20 @@ def test_every_variant_on_an_aligned_problem(oracle):
 @pytest.mark.gpu
 def test_mfma_probe_counts_what_it_claims():
     """The register-only issue loop really executes iters x 8 matrix instructions per
-    wave: with all-ones operands every accumulator element grows by the reduction
-    depth (16 for bf16, 2 for fp32, 64 for int8, 128 for FP8) per instruction."""
+    wave (x 32 for the 16x16 forms): with all-ones operands every accumulator element
+    grows by the reduction depth (16 or 32 for bf16, 2 for fp32, 64 for int8, 128 for
+    FP8) per instruction."""
     iters, blocks = 37, 5
     sink = torch.empty(blocks * 512, dtype=torch.float32, device="cuda")
     ones_h = torch.ones(6 * 64 * 8, device="cuda").to(torch.bfloat16)
     fl = B.gemm_mfma_probe(B.DTYPE_BF16, ones_h, iters, blocks, sink)
     assert fl == 2.0 * 32 * 32 * 16 * 8 * iters * 8 * blocks
     assert (sink.cpu().numpy() == 8 * 16 * iters * 16).all()
+    # the 16x16x32 form (the 256 x 256 and streaming kernels' instruction): 32 per iteration
+    ones_w = torch.ones(12 * 64 * 8, device="cuda").to(torch.bfloat16)
+    fl = B.gemm_mfma_probe(B.PROBE_BF16_16X16X32, ones_w, iters, blocks, sink)
+    assert fl == 2.0 * 16 * 16 * 32 * 32 * iters * 8 * blocks
+    assert (sink.cpu().numpy() == 32 * 4 * iters * 32).all()
     ones_f = torch.ones(6 * 64, device="cuda")
     fl = B.gemm_mfma_probe(B.DTYPE_F32, ones_f, iters, blocks, sink)
     assert fl == 2.0 * 32 * 32 * 2 * 8 * iters * 8 * blocks
