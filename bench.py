@@ -26,24 +26,53 @@ PEAK_F32 = 157.3        # TFLOP/s, fp32 MFMA
 HBM_TBS = 8.0
 # Bytes beyond L2 per launch of the headline kernel, from rocprofv3 --pmc FETCH_SIZE and
 # WRITE_SIZE passes over this same command (profiles/bf16_pingpong_256x256x64_gemm4096_nn.md):
-# (98431.1 KiB x 2.0 + 32768.0 KiB x 1.0) x 1024; the factors are what the same counters
-# read for a plain 1 GiB copy.  Valid for the kernel the counters were taken on only.
-HEADLINE_TRAFFIC = {"bf16_pingpong_256x256x64": (98431.1 * 2.0 + 32768.0 * 1.0) * 1024.0}
+# (FETCH_SIZE KiB x 2.0 + WRITE_SIZE KiB x 1.0) x 1024; the factors are what the same counters
+# read for a plain 1 GiB copy.  The figure belongs to the kernel sources it was taken on:
+# "sources" is the SHA-256 (first 16 hex digits) of the files below at that time, and the
+# bench line reports null as soon as they have changed.
+HEADLINE_TRAFFIC = {"variant": "bf16_pingpong_256x256x64",
+                    "bytes": (98431.1 * 2.0 + 32768.0 * 1.0) * 1024.0,
+                    "files": ["paper_2511_13764_amd/csrc/bf16_pingpong.hip", "paper_2511_13764_amd/csrc/bf16_tiles.hpp"],
+                    "sources": "unset"}
+WARMUP_FLOOR_MS = 100.0  # continuous load before any timed region (clock management settles in ~30 ms)
+
+
+def kernel_sources_digest(files):
+    import hashlib
+    h = hashlib.sha256()
+    for f in files:
+        with open(os.path.join(ROOT, f), "rb") as fh:
+            h.update(fh.read())
+    return h.hexdigest()[:16]
+
+
+def headline_traffic(variant):
+    if variant != HEADLINE_TRAFFIC["variant"]:
+        return None
+    if kernel_sources_digest(HEADLINE_TRAFFIC["files"]) != HEADLINE_TRAFFIC["sources"]:
+        return None
+    return HEADLINE_TRAFFIC["bytes"]
 
 
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     # The chip's clock management needs ~30 ms of continuous load to settle (the first 50
-    # launches of the headline kernel run ~50 % slower than the steady state), hence the
-    # long default warm-up.
+    # launches of the headline kernel run ~50 % slower than the steady state).  Whatever
+    # --warmup says, every timed region is preceded by at least WARMUP_FLOOR_MS of
+    # untimed launches of the same call.
     ap.add_argument("--steps", type=int, default=500)
     ap.add_argument("--warmup", type=int, default=300)
+    ap.add_argument("--print-sources-digest", action="store_true",
+                    help="print the digest that ties HEADLINE_TRAFFIC to the kernel sources, and exit")
     ap.add_argument("--no-others", action="store_true", help="time the headline workload only")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle leg")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="only run three plain 1 GiB device copies (reference for FETCH_SIZE / WRITE_SIZE counters)")
     args = ap.parse_args()
+    if args.print_sources_digest:
+        print(kernel_sources_digest(HEADLINE_TRAFFIC["files"]))
+        return
     if args.gpus != 1:
         print("bench.py: the library runs on one GPU; --gpus must be 1 "
               "(a multi-GPU job would shard M or N across GPUs with no exchange)", file=sys.stderr)
@@ -68,6 +97,14 @@ def main():
 
     def dev(x):
         return torch.from_numpy(x.view(np.int16) if x.dtype == np.uint16 else x).cuda()
+
+    def settle(fn, floor_ms=WARMUP_FLOOR_MS):
+        """Untimed launches for at least floor_ms of GPU work."""
+        t_w = time.perf_counter()
+        while (time.perf_counter() - t_w) * 1e3 < floor_ms:
+            for _ in range(20):
+                fn()
+            torch.cuda.synchronize()
 
     def time_launches(fn, steps, warmup):
         """Wall time per step (sync on both sides) and HIP-event time per launch."""
@@ -108,6 +145,7 @@ def main():
     def step():
         B.gemm_bf16(0, 0, M, N, K, dA, K, dB, N, 0.0, dC, N, 0, workspace=ws)
 
+    settle(step)
     wall, ev = time_launches(step, args.steps, args.warmup)
     variant = B.gemm_variant_name(B.gemm_last_variant())
     split = B.gemm_last_split()
@@ -116,22 +154,29 @@ def main():
     value = flops / wall / 1e12
     achieved = flops / ev / 1e12
 
-    # Matrix-pipe rate of this device with the same instruction and register shape but no
-    # LDS or memory traffic, on operands of the workload's distribution and on zeros: the
-    # rate is set by the chip's power management and depends on the operand values.
+    # Matrix-pipe rate of this device with no LDS or memory traffic, on operands of the
+    # workload's distribution and on zeros: the rate is set by the chip's power management
+    # and depends on the operand values.  Two bf16 forms: 16x16x32 with 32 accumulators (the
+    # instruction and register shape of the headline kernel and of the streaming kernels:
+    # the denominator of frac_of_measured_mfma_rate) and 32x32x16 with 8 accumulators (the
+    # 4-wave 128 x 128 kernel).
     def mfma_rate(dtype, ops):
         sink = torch.empty(2048 * 512, dtype=torch.float32, device="cuda")
         fl = [0.0]
 
         def probe():
             fl[0] = B.gemm_mfma_probe(dtype, ops, 256, 2048, sink)
+        settle(probe, 30.0)
         _, t = time_launches(probe, 20, 3)
         return fl[0] / t / 1e12
 
     g = torch.Generator(device="cuda").manual_seed(20251113)
     ops_n = torch.randn(6 * 64 * 8, device="cuda", generator=g).to(torch.bfloat16)
-    measured = {"bf16_normal_operands": round(mfma_rate(B.DTYPE_BF16, ops_n), 1),
-                "bf16_zero_operands": round(mfma_rate(B.DTYPE_BF16, torch.zeros_like(ops_n)), 1),
+    ops_w = torch.randn(12 * 64 * 8, device="cuda", generator=g).to(torch.bfloat16)
+    measured = {"bf16_16x16x32_normal_operands": round(mfma_rate(B.PROBE_BF16_16X16X32, ops_w), 1),
+                "bf16_16x16x32_zero_operands": round(mfma_rate(B.PROBE_BF16_16X16X32, torch.zeros_like(ops_w)), 1),
+                "bf16_32x32x16_normal_operands": round(mfma_rate(B.DTYPE_BF16, ops_n), 1),
+                "bf16_32x32x16_zero_operands": round(mfma_rate(B.DTYPE_BF16, torch.zeros_like(ops_n)), 1),
                 "f32_uniform_operands": round(mfma_rate(B.DTYPE_F32, torch.rand(6 * 64, device="cuda", generator=g) * 2 - 1), 1),
                 "s8_uniform_operands": round(mfma_rate(B.PROBE_S8, torch.randint(-128, 128, (12 * 64 * 16,), device="cuda",
                                                                                dtype=torch.int8, generator=g)), 1),
@@ -141,17 +186,17 @@ def main():
 
     out = {
         "metric": METRIC, "value": round(value, 2), "unit": "TFLOP/s", "n_gpus": 1,
-        "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(wall * 1e3, 5),
+        "steps": args.steps, "warmup": args.warmup, "warmup_floor_ms": WARMUP_FLOOR_MS, "ms_per_step": round(wall * 1e3, 5),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16",
         "data": "synthetic",
         "config": {"workload": "bf16-in/fp32-acc/bf16-out GEMM M=N=K=4096 row-major (NN) beta=0, N(0,1) inputs",
                    "variant": variant, "split": split},
         "roofline": {"bound": "mfma", "achieved": round(achieved, 2), "peak": PEAK_BF16, "unit": "TFLOP/s",
-                     "frac": round(achieved / PEAK_BF16, 4), "traffic": HEADLINE_TRAFFIC.get(variant),
+                     "frac": round(achieved / PEAK_BF16, 4), "traffic": headline_traffic(variant),
                      "traffic_unit": "bytes per launch (algorithmic: %d)" % (2 * (M * K + K * N + M * N)),
                      "kernel": variant, "us_per_launch": round(ev * 1e6, 2),
                      "us_median": round(med * 1e6, 2), "us_min": round(mn * 1e6, 2),
-                     "frac_of_measured_mfma_rate": round(achieved / measured["bf16_normal_operands"], 4)},
+                     "frac_of_measured_mfma_rate": round(achieved / measured["bf16_16x16x32_normal_operands"], 4)},
         "measured_mfma_rate": measured,
     }
 
@@ -180,12 +225,7 @@ def main():
         others = {}
 
         def record(name, flops_, fn, peak, steps=50, warmup=20, bytes_=None):
-            # warm up for at least 30 ms of GPU work (see --warmup), then time
-            t_w = time.perf_counter()
-            while time.perf_counter() - t_w < 0.03:
-                for _ in range(20):
-                    fn()
-                torch.cuda.synchronize()
+            settle(fn)
             w_, e_ = time_launches(fn, steps, warmup)
             med_, min_ = per_launch(fn, 20, group=1 if e_ > 50e-6 else 20)
             r = {"us": round(e_ * 1e6, 2), "us_median": round(med_ * 1e6, 2), "us_min": round(min_ * 1e6, 2),
@@ -195,7 +235,19 @@ def main():
             if bytes_ is not None:
                 r["hbm_gbs"] = round(bytes_ / e_ / 1e9, 1)
                 r["frac_hbm_peak"] = round(bytes_ / e_ / 1e12 / HBM_TBS, 4)
+                # the attainable roofline of an HBM-bound shape: min(MFMA peak, flop/byte x measured copy rate)
+                r["frac_of_measured_copy"] = round(bytes_ / e_ / 1e9 / copy_gbs, 4)
             others[name] = r
+
+        # Device copy bandwidth of this machine: a plain 1 GiB copy (read + write counted), the
+        # measured stand-in for the 8 TB/s datasheet figure in the HBM-bound rows below.
+        src_c = torch.empty(1 << 28, dtype=torch.float32, device="cuda").normal_()
+        dst_c = torch.empty_like(src_c)
+        settle(lambda: dst_c.copy_(src_c), 30.0)
+        _, t_copy = time_launches(lambda: dst_c.copy_(src_c), 20, 3)
+        copy_gbs = 2.0 * src_c.numel() * 4 / t_copy / 1e9
+        out["hbm_copy_gbs"] = round(copy_gbs, 1)
+        del src_c, dst_c
 
         # fp32 2048^3 with beta = 0.5
         c2 = W.config2_f32_2048()
@@ -262,6 +314,13 @@ def main():
                 record(f"mlp_{which}_M{Mm}" + ("_warm" if Mm <= 128 else ""), 2.0 * Mm * Nn * Kk,
                        lambda: B.gemm_bf16(0, 1, Mm, Nn, Kk, a, Kk, wgt, Kk, 0.0, c, Nn, 0, workspace=ws),
                        PEAK_BF16, steps=30 if Mm == 4096 else 100, bytes_=bytes_ if Mm <= 128 else None)
+                if Mm == 4096 and which == "up":
+                    # the paper's benchmark kernel (Section 6): GEMM + bias + ReLU in one pass
+                    bias = torch.randn(Nn, device="cuda")
+                    record("mlp_up_M4096_bias_relu", 2.0 * Mm * Nn * Kk,
+                           lambda: B.brgemm_fused(B.DTYPE_BF16, 0, 1, Mm, Nn, Kk, 1, a, None, Kk, wgt, None, Kk, 0.0,
+                                                  c, Nn, 0, bias, B.EPI_BIAS | B.EPI_RELU, workspace=ws),
+                           PEAK_BF16, steps=30)
                 if Mm <= 128:
                     turn = [0]
 
