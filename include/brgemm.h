@@ -64,7 +64,8 @@ enum {
     BRGEMM_UNSUPPORTED = -2,         /* reserved; no currently accepted input returns it      */
     BRGEMM_WORKSPACE_TOO_SMALL = -3, /* a forced split variant needs more workspace           */
     BRGEMM_HIP_ERROR = -4,           /* launch failed; see gemm_last_hip_error()              */
-    BRGEMM_MISALIGNED_WORKSPACE = -5
+    BRGEMM_MISALIGNED_WORKSPACE = -5,
+    BRGEMM_SCRATCH_TOO_SMALL = -6    /* gemm_bf16_noalloc: split partial sums exceed its buffer */
 };
 
 /* Element types, for gemm_workspace_bytes(). */
@@ -93,6 +94,27 @@ int gemm_bf16(int transA, int transB, int64_t M, int64_t N, int64_t K,
               const uint16_t *A, int64_t lda, const uint16_t *B, int64_t ldb,
               float beta, void *C, int64_t ldc, int c_is_f32,
               void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * gemm_bf16 for callers that cannot allocate device memory and have no workspace to
+ * hand over: code under HIP graph capture, tight serving loops, harnesses that forbid
+ * hipMalloc.  Same operation, arguments, plan and results as gemm_bf16 called with a
+ * workspace of gemm_workspace_bytes(); the partial sums of a reduction split (skinny-M
+ * and small-grid shapes) go to a buffer that is part of the library's code object,
+ * BRGEMM_NOALLOC_SCRATCH_BYTES of device memory per GPU, held until the process ends.
+ * The call makes no hipMalloc / hipFree and calls no allocating routine.  A problem
+ * whose plan needs split * M * N * 4 bytes beyond that size is refused with
+ * BRGEMM_SCRATCH_TOO_SMALL and nothing is launched (M = 128, N = 11008 needs 11 MiB;
+ * problems that run unsplit, such as 4096^3, need none and are always accepted).
+ * The first call on a device looks the buffer's address up (make one call before
+ * starting a graph capture).  All calls on one GPU share the buffer: calls that may
+ * overlap there (different streams, different host threads) race; order them on one
+ * stream.  Its contents are overwritten by every split call and need no clearing.
+ */
+#define BRGEMM_NOALLOC_SCRATCH_BYTES (32u << 20)
+int gemm_bf16_noalloc(int transA, int transB, int64_t M, int64_t N, int64_t K,
+                      const uint16_t *A, int64_t lda, const uint16_t *B, int64_t ldb,
+                      float beta, void *C, int64_t ldc, int c_is_f32, void *stream);
 
 /*
  * The same for IEEE binary16 operands (Section 2.2 names FP16 beside BF16 among

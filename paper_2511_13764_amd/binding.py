@@ -23,6 +23,8 @@ UNSUPPORTED = -2
 WORKSPACE_TOO_SMALL = -3
 HIP_ERROR = -4
 MISALIGNED_WORKSPACE = -5
+SCRATCH_TOO_SMALL = -6
+NOALLOC_SCRATCH_BYTES = 32 << 20
 DTYPE_F32, DTYPE_BF16, DTYPE_F16 = 0, 1, 2
 PROBE_S8, PROBE_F8, PROBE_BF16_16X16X32 = 3, 4, 5
 EPI_NONE, EPI_BIAS, EPI_RELU = 0, 1, 2
@@ -31,7 +33,7 @@ EXPORTS = ["gemm_f32", "gemm_bf16", "brgemm_bf16", "brgemm_fused", "gemm_workspa
            "gemm_strerror", "gemm_last_hip_error", "gemm_force_variant", "gemm_variant_name",
            "gemm_last_variant", "gemm_last_split", "gemm_mfma_probe", "gemm_pack_vnni_bf16",
            "gemm_packed_b_bytes", "gemm_pack_b_bf16", "gemm_bf16_packed", "gemm_bf16_batched",
-           "gemm_f32_batched", "gemm_f16", "gemm_s8", "gemm_query_plan", "gemm_f8"]
+           "gemm_f32_batched", "gemm_f16", "gemm_s8", "gemm_query_plan", "gemm_f8", "gemm_bf16_noalloc"]
 
 _lib = None
 
@@ -57,6 +59,8 @@ def load():
     lib.gemm_f32.argtypes = [ci, ci, i64, i64, i64, vp, i64, vp, i64, cf, vp, i64, vp, sz, vp]
     lib.gemm_bf16.restype = ci
     lib.gemm_bf16.argtypes = [ci, ci, i64, i64, i64, vp, i64, vp, i64, cf, vp, i64, ci, vp, sz, vp]
+    lib.gemm_bf16_noalloc.restype = ci
+    lib.gemm_bf16_noalloc.argtypes = [ci, ci, i64, i64, i64, vp, i64, vp, i64, cf, vp, i64, ci, vp]
     lib.gemm_f16.restype = ci
     lib.gemm_f16.argtypes = [ci, ci, i64, i64, i64, vp, i64, vp, i64, cf, vp, i64, ci, vp, sz, vp]
     lib.gemm_f8.restype = ci
@@ -145,6 +149,12 @@ def gemm_bf16(transA, transB, M, N, K, A, lda, B, ldb, beta, C, ldc, c_is_f32, w
     rc = load().gemm_bf16(transA, transB, M, N, K, _ptr(A), lda, _ptr(B), ldb, beta, _ptr(C), ldc,
                           int(bool(c_is_f32)), ws, nb, _stream(stream))
     return _check(rc, "gemm_bf16", check)
+
+
+def gemm_bf16_noalloc(transA, transB, M, N, K, A, lda, B, ldb, beta, C, ldc, c_is_f32, stream=None, check=True):
+    rc = load().gemm_bf16_noalloc(transA, transB, M, N, K, _ptr(A), lda, _ptr(B), ldb, beta, _ptr(C), ldc,
+                                  int(bool(c_is_f32)), _stream(stream))
+    return _check(rc, "gemm_bf16_noalloc", check)
 
 
 def gemm_f16(transA, transB, M, N, K, A, lda, B, ldb, beta, C, ldc, c_is_f32, workspace=None, stream=None,

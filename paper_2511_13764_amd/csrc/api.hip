@@ -4,8 +4,16 @@
 #include "../../include/brgemm.h"
 #include "common.hpp"
 #include "variants.hpp"
+#include <mutex>
 
 using namespace brg;
+
+// Library-owned partial-sum buffer of gemm_bf16_noalloc: device memory that is part of
+// the code object, so no allocation call is ever made for it.  In host code this name
+// is only a handle for hipGetSymbolAddress; the device address it yields (one per GPU)
+// is what kernels and copies get.
+constexpr size_t kScratchBytes = (size_t)BRGEMM_NOALLOC_SCRATCH_BYTES;
+static __device__ __align__(256) unsigned char scratch[kScratchBytes];
 
 namespace {
 
@@ -62,7 +70,38 @@ int finish(hipError_t e)
     return BRGEMM_OK;
 }
 
-int run(Problem &p, void *workspace, size_t workspace_bytes, bool need_offsets)
+// Device address of `scratch` on the current GPU, looked up once per device.
+constexpr int kMaxDevices = 64;
+std::mutex scratch_mutex;
+void *scratch_ptr[kMaxDevices] = {nullptr};
+
+int scratch_of_current_device(void **out)
+{
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e == hipSuccess && (dev < 0 || dev >= kMaxDevices))
+        e = hipErrorInvalidDevice;
+    if (e == hipSuccess) {
+        std::lock_guard<std::mutex> lock(scratch_mutex);
+        if (!scratch_ptr[dev]) {
+            void *ptr = nullptr;
+            e = hipGetSymbolAddress((void **)&ptr, HIP_SYMBOL(scratch));
+            if (e == hipSuccess && !ptr)
+                e = hipErrorInvalidSymbol;
+            if (e == hipSuccess)
+                scratch_ptr[dev] = ptr;
+        }
+        *out = scratch_ptr[dev];
+    }
+    if (e != hipSuccess) {
+        tl_last_hip_error = (int)e;
+        return BRGEMM_HIP_ERROR;
+    }
+    return BRGEMM_OK;
+}
+
+// preset: a plan the caller has already chosen for this problem (nullptr: choose here).
+int run(Problem &p, void *workspace, size_t workspace_bytes, bool need_offsets, const Plan *preset = nullptr)
 {
     if (p.nmat == 0)
         p.nmat = 1;
@@ -80,7 +119,10 @@ int run(Problem &p, void *workspace, size_t workspace_bytes, bool need_offsets)
     }
 
     Plan plan;
-    rc = choose_plan(p, workspace_bytes, tl_forced_variant, tl_forced_split, &plan);
+    if (preset)
+        plan = *preset;
+    else
+        rc = choose_plan(p, workspace_bytes, tl_forced_variant, tl_forced_split, &plan);
     if (rc != BRGEMM_OK)
         return rc;
     p.split = plan.split;
@@ -126,6 +168,37 @@ int gemm_bf16(int transA, int transB, int64_t M, int64_t N, int64_t K,
     p.beta = beta; p.C = C; p.ldc = ldc; p.c_f32 = c_is_f32 ? 1 : 0;
     p.stream = (hipStream_t)stream;
     return run(p, workspace, workspace_bytes, false);
+}
+
+int gemm_bf16_noalloc(int transA, int transB, int64_t M, int64_t N, int64_t K,
+                      const uint16_t *A, int64_t lda, const uint16_t *B, int64_t ldb,
+                      float beta, void *C, int64_t ldc, int c_is_f32, void *stream)
+{
+    Problem p{};
+    p.in_bf16 = 1; p.transA = transA; p.transB = transB;
+    p.M = M; p.N = N; p.K = K; p.batch = 1; p.nmat = 1;
+    p.A = A; p.lda = lda; p.B = B; p.ldb = ldb;
+    p.beta = beta; p.C = C; p.ldc = ldc; p.c_f32 = c_is_f32 ? 1 : 0;
+    p.stream = (hipStream_t)stream;
+    int rc = validate(p, nullptr, 0, false);
+    if (rc != BRGEMM_OK)
+        return rc;
+    // The plan gemm_bf16 would take with all the workspace it can use must fit the
+    // library's own buffer; a larger problem is refused, not run with another plan.
+    Plan plan{V_GENERIC, 1};
+    const bool work = M > 0 && N > 0 && K > 0;
+    if (work) {
+        rc = choose_plan(p, ~(size_t)0, tl_forced_variant, tl_forced_split, &plan);
+        if (rc != BRGEMM_OK)
+            return rc;
+        if (plan.split > 1 && (size_t)plan.split * (size_t)M * (size_t)N * sizeof(float) > kScratchBytes)
+            return BRGEMM_SCRATCH_TOO_SMALL;
+    }
+    void *ws = nullptr;
+    rc = scratch_of_current_device(&ws);
+    if (rc != BRGEMM_OK)
+        return rc;
+    return run(p, ws, kScratchBytes, false, work ? &plan : nullptr);
 }
 
 int gemm_f16(int transA, int transB, int64_t M, int64_t N, int64_t K,
@@ -336,6 +409,7 @@ const char *gemm_strerror(int code)
     case BRGEMM_WORKSPACE_TOO_SMALL: return "workspace too small for the forced split";
     case BRGEMM_HIP_ERROR: return "HIP launch error (see gemm_last_hip_error)";
     case BRGEMM_MISALIGNED_WORKSPACE: return "workspace is not 256-byte aligned";
+    case BRGEMM_SCRATCH_TOO_SMALL: return "the problem's reduction split needs more than the library's built-in scratch buffer (gemm_bf16_noalloc)";
     default: return "unknown error code";
     }
 }
