@@ -261,15 +261,27 @@ __device__ __forceinline__ void pp_body(const Bf16Args &p)
     float *part = to_partial ? p.partial + (int64_t)blockIdx.y * p.M * p.N : nullptr;
     const bool vec = to_partial ? ((p.N & 3) == 0)
                                 : ((p.epi.ldc & 3) == 0 && (((uintptr_t)p.epi.C) & 15) == 0);
-    // Fast path for the common case (bf16 C, beta == 0, no bias / ReLU, aligned, no
-    // overhang in N): narrow in registers with v_cvt_pk_bf16_f32, stage bf16 (136-byte
-    // row pitch: conflict-free 64-bit writes), read back 16 bytes per lane and store
-    // 8 rows x 128 bytes per instruction.
-    const bool fast_bf16 = !to_partial && !p.epi.c_f32 && p.epi.beta == 0.0f && !p.epi.bias && !p.epi.relu &&
+    // Fast path for the common case (16-bit C, beta == 0, aligned, no overhang in N;
+    // bias and ReLU - the fused kernel of Section 6 - included): bias and ReLU in
+    // registers, narrowing with v_cvt_pk_bf16_f32, staging as 16-bit values (136-byte row
+    // pitch: conflict-free 64-bit writes), read back 16 bytes per lane, 8 rows x 128
+    // bytes per store instruction.
+    const bool fast_bf16 = !to_partial && !p.epi.c_f32 && !p.epi.c_i32 && p.epi.beta == 0.0f &&
                            (p.epi.ldc & 7) == 0 && (((uintptr_t)p.epi.C) & 15) == 0 && n0 + PP_BN <= p.N;
     if (fast_bf16) {
         LDS_AS char *stage_h = smem + (uint32_t)w * (32 * 136);
         uint16_t *crow = (uint16_t *)p.epi.C + (m0 + wm * PP_WM) * p.epi.ldc + n0 + wn * PP_WN;
+        // this lane's 4 columns of each of the 4 accumulator columns: 16 bias values
+        f32x4 bias4[PP_TN];
+        const bool has_bias = p.epi.bias != nullptr;
+        const bool relu = p.epi.relu != 0;
+        if (has_bias) {
+            const float *bp = p.epi.bias + n0 + wn * PP_WN + 4 * (lane >> 4);
+            const bool bvec = (((uintptr_t)p.epi.bias) & 15) == 0;
+#pragma unroll
+            for (int a = 0; a < PP_TN; ++a)
+                bias4[a] = bvec ? *(const f32x4 *)(bp + 16 * a) : f32x4{bp[16 * a], bp[16 * a + 1], bp[16 * a + 2], bp[16 * a + 3]};
+        }
         static_for<0, PP_TM / 2>([&](auto bc) {
             constexpr int b2 = decltype(bc)::value;
             asm volatile("" ::: "memory");
@@ -277,7 +289,14 @@ __device__ __forceinline__ void pp_body(const Bf16Args &p)
                 constexpr int bb = decltype(aq)::value / PP_TN, a = decltype(aq)::value % PP_TN;
                 const int row = 16 * bb + (lane & 15);
                 const int col = 16 * a + 4 * (lane >> 4);
-                const f32x4 v = acc[a][2 * b2 + bb];
+                f32x4 v = acc[a][2 * b2 + bb];
+                if (has_bias)
+                    v += bias4[a];
+                if (relu) {
+#pragma unroll
+                    for (int e = 0; e < 4; ++e)
+                        v[e] = v[e] < 0.0f ? 0.0f : v[e];       // NaN stays NaN
+                }
                 const u32x2 pk = {KIND == KIND_F16 ? pack_f16x2(v[0], v[1]) : pack_bf16x2(v[0], v[1]),
                                   KIND == KIND_F16 ? pack_f16x2(v[2], v[3]) : pack_bf16x2(v[2], v[3])};
                 *(LDS_AS u32x2 *)(stage_h + row * 136 + col * 2) = pk;

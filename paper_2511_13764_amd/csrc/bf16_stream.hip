@@ -35,7 +35,10 @@ constexpr int ST_STAGES = 3;
 template <int BM>
 struct StreamWaves { static constexpr int value = BM >= 64 ? 8 : 4; };
 
-template <int BM, bool A_KMAJ, int B_LAY, int KIND>
+// STAGES: depth of the LDS ring (three, see above; a six-deep ring for batch-reduce
+// calls over scattered tiles measured the same as three: there the time is a chain of
+// fixed latencies - launch, offsets, first tiles, partial tiles, second launch).
+template <int BM, bool A_KMAJ, int B_LAY, int KIND, int STAGES = ST_STAGES>
 __global__ void __launch_bounds__(StreamWaves<BM>::value * 64)
 bf16_stream_kernel(Bf16Args p)
 {
@@ -49,8 +52,8 @@ bf16_stream_kernel(Bf16Args p)
     constexpr uint32_t A_BYTES = BM * BK * 2, B_BYTES = ST_BN * BK * 2;
     constexpr uint32_t STAGE = A_BYTES + B_BYTES;
     constexpr int L = ATile::kPerWave + BTile::kPerWave;        // loads per wave per block
-    constexpr int stages = ST_STAGES;
-    static_assert((ST_STAGES - 2) * L <= 63, "outstanding loads must fit vmcnt");
+    constexpr int stages = STAGES;
+    static_assert((STAGES - 2) * L <= 63, "outstanding loads must fit vmcnt");
 
     extern __shared__ __attribute__((aligned(1024))) char smem_generic[];
     LDS_AS char *smem = (LDS_AS char *)smem_generic;
@@ -61,14 +64,16 @@ bf16_stream_kernel(Bf16Args p)
     const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wm = w / WGN, wn = w % WGN;
 
-    const int tm = (int)blockIdx.x % p.tiles_m, tn = (int)blockIdx.x / p.tiles_m;
+    int tile, slice;
+    slice_major_coords(p.tiles_m * p.tiles_n, tile, slice);
+    const int tm = tile % p.tiles_m, tn = tile / p.tiles_m;
     const int64_t m0 = (int64_t)tm * BM, n0 = (int64_t)tn * ST_BN;
 
     // Reduction range of this workgroup: flattened (batch, k-block) iterations.
     const int kblocks = (int)(p.K / BK);
     const int total = (int)p.batch * kblocks;
     const int per = (total + p.split - 1) / p.split;
-    const int it_begin = (int)blockIdx.y * per;
+    const int it_begin = slice * per;
     const int it_end = (it_begin + per < total) ? it_begin + per : total;
     const int n_iter = it_end > it_begin ? it_end - it_begin : 0;
 
@@ -88,20 +93,26 @@ bf16_stream_kernel(Bf16Args p)
     // Load cursor: (batch index, k-block) of the next block to request and its pointers.
     int ld_i = n_iter > 0 ? it_begin / kblocks : 0;
     int ld_kb = n_iter > 0 ? it_begin - ld_i * kblocks : 0;
-    const uint16_t *ld_a = uniform_ptr(p.A + (p.A_off ? p.A_off[ld_i] : 0) + a_origin + ld_kb * a_kstep);
-    const uint16_t *ld_b = uniform_ptr(p.B + (p.B_off ? p.B_off[ld_i] : 0) + b_origin + ld_kb * b_kstep);
-    int ld_slot = 0;
-    // Tile offsets live in device memory: if one is not a multiple of 8 elements the
-    // whole workgroup stages its blocks through registers with 2-byte loads instead
-    // (same LDS image; those loads complete before the stores, so the counted waits
-    // below simply find nothing outstanding).
+    TileOffsets offs_a, offs_b;                 // this wave's window of the tile offsets
+    // Tile offsets live in device memory: if one of this workgroup's tiles does not
+    // start at a multiple of 8 elements the workgroup stages its blocks through
+    // registers with 2-byte loads instead (same LDS image; those loads complete before
+    // the stores, so the counted waits below simply find nothing outstanding).  Every
+    // wave looks at all of the workgroup's tiles (the first 64 are the window it keeps),
+    // so all waves reach the same verdict without a barrier.
     bool direct = true;
     if (p.A_off) {
-        int ok = 1;
-        for (int i = tid; i < (int)p.batch; i += NW * 64)
-            ok &= (((p.A_off[i] | p.B_off[i]) & 7) == 0);
-        direct = __syncthreads_and(ok) != 0;
+        offs_a.init(p.A_off, p.batch, ld_i, lane);
+        offs_b.init(p.B_off, p.batch, ld_i, lane);
+        const int last_i = n_iter > 0 ? (it_end - 1) / kblocks : ld_i;
+        int bad = (ld_i + lane <= last_i) && (((offs_a.lo | offs_b.lo) & 7u) != 0);
+        for (int i = ld_i + 64 + lane; i <= last_i; i += 64)
+            bad |= (((p.A_off[i] | p.B_off[i]) & 7) != 0);
+        direct = __builtin_amdgcn_ballot_w64(bad != 0) == 0;
     }
+    const uint16_t *ld_a = uniform_ptr(p.A + (p.A_off ? offs_a.get(ld_i, lane) : 0) + a_origin + ld_kb * a_kstep);
+    const uint16_t *ld_b = uniform_ptr(p.B + (p.B_off ? offs_b.get(ld_i, lane) : 0) + b_origin + ld_kb * b_kstep);
+    int ld_slot = 0;
     auto staged16 = [&](const char *gc, uint32_t lds_byte) {
         const uint16_t *g = (const uint16_t *)gc;
         s16x8 v;
@@ -134,8 +145,8 @@ bf16_stream_kernel(Bf16Args p)
             ld_kb = 0;
             ++ld_i;
             if (p.A_off && ld_i < (int)p.batch) {
-                ld_a = uniform_ptr(p.A + p.A_off[ld_i] + a_origin);
-                ld_b = uniform_ptr(p.B + p.B_off[ld_i] + b_origin);
+                ld_a = uniform_ptr(p.A + offs_a.get(ld_i, lane) + a_origin);
+                ld_b = uniform_ptr(p.B + offs_b.get(ld_i, lane) + b_origin);
             }
         } else {
             ld_a += a_kstep;
@@ -177,7 +188,7 @@ bf16_stream_kernel(Bf16Args p)
         }
         // Block t has landed once only the stages - 2 younger blocks are outstanding.
         if (t + stages - 2 < n_iter)
-            wait_vmcnt_le<(ST_STAGES - 2) * L>();
+            wait_vmcnt_le<(STAGES - 2) * L>();
         else
             wait_vmcnt0();                          // tail: fewer blocks than slots remain
         if (!direct)
@@ -215,7 +226,7 @@ bf16_stream_kernel(Bf16Args p)
             mfma_half(H1);
     }
 
-    store_wave_tile16<TM, TN>(p, acc, m0 + wm * WM + (lane & 15), n0 + wn * WN + 4 * (lane >> 4), (int)blockIdx.y);
+    store_wave_tile16<TM, TN>(p, acc, m0 + wm * WM + (lane & 15), n0 + wn * WN + 4 * (lane >> 4), slice);
 }
 
 // ---------------------------------------------------------------------------
@@ -249,11 +260,12 @@ constexpr int S128_EPI_LD = ST_BN + 4;           // floats per staged row (528 B
 
 // All 512 threads: the staged 128 x 128 fp32 tile, two rows per wave and instruction, to
 // C (beta, bias, ReLU, narrowing) or to this split's partial sums.
-__device__ __forceinline__ void stream128_store_tile(const Bf16Args &p, LDS_AS char *smem, int tid, int64_t m0, int64_t n0)
+__device__ __forceinline__ void stream128_store_tile(const Bf16Args &p, LDS_AS char *smem, int tid, int64_t m0, int64_t n0,
+                                                     int slice)
 {
     LDS_AS float *stage = (LDS_AS float *)smem;
     const bool to_partial = p.split > 1;
-    float *part = to_partial ? p.partial + (int64_t)blockIdx.y * p.M * p.N : nullptr;
+    float *part = to_partial ? p.partial + (int64_t)slice * p.M * p.N : nullptr;
     const bool vec = to_partial ? ((p.N & 3) == 0) : ((p.epi.ldc & 3) == 0 && (((uintptr_t)p.epi.C) & 15) == 0);
 #pragma unroll 2
     for (int i = 0; i < 8; ++i) {
@@ -293,14 +305,15 @@ bf16_stream128_kernel(Bf16Args p)
     const int lane = tid & 63;
     const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
 
-    int tm, tn;
-    tile_coords(blockIdx.x, p.tiles_m, p.tiles_n, tm, tn);
+    int tile, slice, tm, tn;
+    slice_major_coords(p.tiles_m * p.tiles_n, tile, slice);
+    group_walk(tile, p.tiles_m, p.tiles_n, tm, tn);
     const int64_t m0 = (int64_t)tm * BM, n0 = (int64_t)tn * ST_BN;
 
     const int kblocks = (int)(p.K / BK);
     const int total = (int)p.batch * kblocks;
     const int per = (total + p.split - 1) / p.split;
-    const int it_begin = (int)blockIdx.y * per;
+    const int it_begin = slice * per;
     const int it_end = (it_begin + per < total) ? it_begin + per : total;
     const int n_iter = it_end > it_begin ? it_end - it_begin : 0;
 
@@ -333,8 +346,13 @@ bf16_stream128_kernel(Bf16Args p)
         const int64_t a_origin = ATile::origin(m0, p.lda), b_origin = BTile::origin(n0, p.ldb);
         int ld_i = n_iter > 0 ? it_begin / kblocks : 0;
         int ld_kb = n_iter > 0 ? it_begin - ld_i * kblocks : 0;
-        const uint16_t *ld_a = uniform_ptr(p.A + (p.A_off ? p.A_off[ld_i] : 0) + a_origin + ld_kb * a_kstep);
-        const uint16_t *ld_b = uniform_ptr(p.B + (p.B_off ? p.B_off[ld_i] : 0) + b_origin + ld_kb * b_kstep);
+        TileOffsets offs_a, offs_b;             // this wave's window of the tile offsets
+        if (p.A_off) {
+            offs_a.init(p.A_off, p.batch, ld_i, lane);
+            offs_b.init(p.B_off, p.batch, ld_i, lane);
+        }
+        const uint16_t *ld_a = uniform_ptr(p.A + (p.A_off ? offs_a.get(ld_i, lane) : 0) + a_origin + ld_kb * a_kstep);
+        const uint16_t *ld_b = uniform_ptr(p.B + (p.B_off ? offs_b.get(ld_i, lane) : 0) + b_origin + ld_kb * b_kstep);
         int ld_slot = 0;
         auto issue_one = [&](const char *base, uint32_t src, uint32_t dst) {
             if (direct) {
@@ -360,8 +378,8 @@ bf16_stream128_kernel(Bf16Args p)
                 ld_kb = 0;
                 ++ld_i;
                 if (p.A_off && ld_i < (int)p.batch) {
-                    ld_a = uniform_ptr(p.A + p.A_off[ld_i] + a_origin);
-                    ld_b = uniform_ptr(p.B + p.B_off[ld_i] + b_origin);
+                    ld_a = uniform_ptr(p.A + offs_a.get(ld_i, lane) + a_origin);
+                    ld_b = uniform_ptr(p.B + offs_b.get(ld_i, lane) + b_origin);
                 }
             } else {
                 ld_a += a_kstep;
@@ -384,7 +402,7 @@ bf16_stream128_kernel(Bf16Args p)
         }
         block_sync();                               // E1
         block_sync();                               // E2: the staged tile is complete
-        stream128_store_tile(p, smem, tid, m0, n0);
+        stream128_store_tile(p, smem, tid, m0, n0, slice);
         return;
     }
 
@@ -449,7 +467,7 @@ bf16_stream128_kernel(Bf16Args p)
                 acc[a][b];
     wait_lgkmcnt0();
     block_sync();                                   // E2
-    stream128_store_tile(p, smem, tid, m0, n0);
+    stream128_store_tile(p, smem, tid, m0, n0, slice);
 }
 
 template <int BM>
@@ -497,7 +515,7 @@ hipError_t launch_stream(const Problem &p)
         }
 #undef BRG_PICK
     }
-    static thread_local const void *configured[16] = {nullptr};
+    static thread_local const void *configured[24] = {nullptr};
     bool done = false;
     for (const void *c : configured)
         done = done || c == (const void *)kern;

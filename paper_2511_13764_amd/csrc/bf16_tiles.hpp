@@ -137,6 +137,44 @@ __device__ __forceinline__ const uint16_t *uniform_ptr(const uint16_t *p)
     return (const uint16_t *)(((uint64_t)hi << 32) | lo);
 }
 
+// Tile offsets of a batch-reduce call (Section 2.1: the tiles of one call need not be
+// contiguous), 64 at a time in two registers of the wave: lane l holds the offset of
+// tile `base + l`, and a wave-uniform tile index is served by v_readlane.  With
+// 64-deep tiles every k-block starts a new tile; fetched one by one from memory, each
+// offset is a dependent global load in front of that block's loads.  Here that
+// latency is paid once per 64 tiles.
+struct TileOffsets {
+    const int64_t *off;
+    int last;               // batch - 1
+    int base;
+    uint32_t lo, hi;
+
+    __device__ __forceinline__ void refill(int first, int lane)
+    {
+        const int i = first + lane < last ? first + lane : last;
+        const uint64_t v = (uint64_t)off[i];
+        lo = (uint32_t)v;
+        hi = (uint32_t)(v >> 32);
+        base = first;
+    }
+    __device__ __forceinline__ void init(const int64_t *offsets, int64_t batch, int first, int lane)
+    {
+        off = offsets;
+        last = (int)batch - 1;
+        refill(first, lane);
+    }
+    // i: wave-uniform tile index, base <= i < batch.
+    __device__ __forceinline__ int64_t get(int i, int lane)
+    {
+        if (i - base >= 64)
+            refill(i, lane);
+        const int l = i - base;
+        const uint32_t a = (uint32_t)__builtin_amdgcn_readlane((int)lo, l);
+        const uint32_t b = (uint32_t)__builtin_amdgcn_readlane((int)hi, l);
+        return (int64_t)(((uint64_t)b << 32) | a);
+    }
+};
+
 // The same load in its scalar-base form: a wave-uniform 64-bit base in SGPRs plus
 // a 32-bit per-lane byte offset.  With 64-bit per-lane addresses the load's
 // address read competes with the MFMAs of the other wave on the SIMD for register
@@ -390,13 +428,10 @@ struct TileOf<EXTENT, NW, LAY_PACKED> { typedef PackedTile<EXTENT, NW> type; };
 // its own L2), so workgroup w is renumbered to t = (w % 8) * (T/8) + w / 8: every
 // XCD then owns a contiguous run of logical tiles, and logical tiles are walked in
 // groups of GM tile-rows so that a run shares few A row-panels and B column-panels.
-__device__ __forceinline__ void tile_coords(int w, int tiles_m, int tiles_n, int &tm, int &tn)
+// Logical tile number t -> (tm, tn): tiles are walked in groups of GM tile-rows, so a
+// contiguous run of logical tiles shares few A row-panels and B column-panels.
+__device__ __forceinline__ void group_walk(int t, int tiles_m, int tiles_n, int &tm, int &tn)
 {
-    const int T = tiles_m * tiles_n;
-    const int T8 = T & ~7;
-    int t = w;
-    if (w < T8)
-        t = (w & 7) * (T8 >> 3) + (w >> 3);
     constexpr int GM = 4;
     const int per_group = GM * tiles_n;
     const int group = t / per_group;
@@ -405,6 +440,35 @@ __device__ __forceinline__ void tile_coords(int w, int tiles_m, int tiles_n, int
     const int in_group = t - group * per_group;
     tm = first_m + in_group % gsize;
     tn = in_group / gsize;
+}
+
+__device__ __forceinline__ void tile_coords(int w, int tiles_m, int tiles_n, int &tm, int &tn)
+{
+    const int T = tiles_m * tiles_n;
+    const int T8 = T & ~7;
+    int t = w;
+    if (w < T8)
+        t = (w & 7) * (T8 >> 3) + (w >> 3);
+    group_walk(t, tiles_m, tiles_n, tm, tn);
+}
+
+// Work assignment of a launch whose grid is (tiles, split): which tile and which slice
+// of the reduction this workgroup takes.  Workgroups are dealt to the XCDs round-robin
+// in launch order (x fastest), so launch index L is renumbered to
+// L' = (L % 8) * (W / 8) + L / 8 and L' is read slice-major: every XCD owns a
+// contiguous run of (slice, tile) pairs, i.e. as few reduction slices as possible.
+// With a split of 8 each XCD's L2 then holds one eighth of the tiles of a
+// batch-reduce call instead of all of them (8 MiB of scattered tiles do not fit one
+// 4 MiB L2; fetched by every XCD they made each 64-deep block wait for the
+// last-level cache).
+__device__ __forceinline__ void slice_major_coords(int tiles, int &tile, int &slice)
+{
+    const int W = (int)(gridDim.x * gridDim.y);
+    const int L = (int)(blockIdx.x + gridDim.x * blockIdx.y);
+    const int W8 = W & ~7;
+    const int Lp = L < W8 ? (L & 7) * (W8 >> 3) + (L >> 3) : L;
+    slice = Lp / tiles;
+    tile = Lp - slice * tiles;
 }
 
 template <int I, int N, typename F>
