@@ -357,3 +357,30 @@ void oracle_f8e4m3_widen(const uint8_t *src, int64_t count, float *dst)
     for (int64_t i = 0; i < count; ++i)
         dst[i] = (float)oracle_f8e4m3_to_f64(src[i]);
 }
+
+/*
+ * The other 8-bit float of the same family (OCP "E5M2": 1 sign, 5 exponent bits with bias
+ * 15, 2 fraction bits; exponent 31 holds the infinities (fraction 0) and NaN (fraction
+ * != 0), largest finite value 57344, subnormals f/4 * 2^-14).  Section 5(c) again: one
+ * more packed type through the same structure.  Decoded on values, exactly; every E5M2
+ * value is exactly representable in fp32 (and in binary16, whose top byte it is).
+ */
+double oracle_f8e5m2_to_f64(uint8_t b)
+{
+    const int sign = b >> 7, e = (b >> 2) & 31, f = b & 3;
+    double v;
+    if (e == 31)
+        v = f ? NAN : INFINITY;
+    else if (e == 0)
+        v = ldexp((double)f, -16);                   /* subnormal: f/4 * 2^-14 */
+    else
+        v = ldexp(1.0 + (double)f / 4.0, e - 15);
+    return sign ? -v : v;
+}
+
+/* Widen `count` E5M2 bytes to fp32 (exact). */
+void oracle_f8e5m2_widen(const uint8_t *src, int64_t count, float *dst)
+{
+    for (int64_t i = 0; i < count; ++i)
+        dst[i] = (float)oracle_f8e5m2_to_f64(src[i]);
+}

@@ -54,6 +54,10 @@ def _load():
     lib.oracle_f8e4m3_to_f64.argtypes = [ctypes.c_uint8]
     lib.oracle_f8e4m3_widen.restype = None
     lib.oracle_f8e4m3_widen.argtypes = [vp, i64, vp]
+    lib.oracle_f8e5m2_to_f64.restype = ctypes.c_double
+    lib.oracle_f8e5m2_to_f64.argtypes = [ctypes.c_uint8]
+    lib.oracle_f8e5m2_widen.restype = None
+    lib.oracle_f8e5m2_widen.argtypes = [vp, i64, vp]
     lib.oracle_gemm_s8.restype = cint
     lib.oracle_gemm_s8.argtypes = [cint, cint, i64, i64, i64, vp, i64, vp, i64, cint, vp, i64, vp]
     lib.oracle_pack_vnni.restype = cint
@@ -222,4 +226,17 @@ def f8e4m3_widen(a):
     a = np.ascontiguousarray(a, dtype=np.uint8)
     out = np.empty(a.shape, dtype=np.float32)
     _load().oracle_f8e4m3_widen(_ptr(a), a.size, _ptr(out))
+    return out
+
+
+def f8e5m2_to_f64(byte):
+    """Exact value of one FP8 E5M2 pattern."""
+    return float(_load().oracle_f8e5m2_to_f64(int(byte)))
+
+
+def f8e5m2_widen(a):
+    """uint8 array of E5M2 patterns -> float32 array of the same shape (exact)."""
+    a = np.ascontiguousarray(a, dtype=np.uint8)
+    out = np.empty(a.shape, dtype=np.float32)
+    _load().oracle_f8e5m2_widen(_ptr(a), a.size, _ptr(out))
     return out

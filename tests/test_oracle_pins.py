@@ -595,3 +595,49 @@ def test_f8e4m3_decoder_hand_values_and_structure(oracle):
         assert (t[ok] == w[ok]).all() and (np.isnan(t) == np.isnan(w)).all()
     except (ImportError, AttributeError, RuntimeError):
         pass
+
+
+# ---------------------------------------------------------------- FP8 E5M2 decoder
+
+def test_f8e5m2_decoder_hand_values_and_structure(oracle):
+    d = oracle.f8e5m2_to_f64
+    assert d(0x00) == 0.0 and d(0x80) == 0.0 and np.signbit(d(0x80))
+    assert d(0x01) == 2.0 ** -16 and d(0x03) == 3 * 2.0 ** -16        # subnormals
+    assert d(0x04) == 2.0 ** -14                                      # smallest normal
+    assert d(0x3C) == 1.0 and d(0x3D) == 1.25 and d(0x3E) == 1.5 and d(0xBC) == -1.0
+    assert d(0x40) == 2.0 and d(0x42) == 3.0 and d(0x44) == 4.0
+    assert d(0x7B) == 57344.0 and d(0xFB) == -57344.0                 # largest finite
+    assert d(0x7C) == np.inf and d(0xFC) == -np.inf
+    assert all(np.isnan(d(b)) for b in (0x7D, 0x7E, 0x7F, 0xFD, 0xFE, 0xFF))
+    vals = [d(b) for b in range(0x7D)]
+    assert all(x < y for x, y in zip(vals, vals[1:]))                # strictly increasing up to +inf
+    for b in range(0x7D):
+        assert d(b | 0x80) == -d(b)
+    # an E5M2 pattern is the top byte of the binary16 pattern of the same value: the
+    # textbook definition, checked against numpy's binary16 decoding of byte << 8
+    w = oracle.f8e5m2_widen(np.arange(256, dtype=np.uint8))
+    half = (np.arange(256, dtype=np.uint16) << 8).view(np.float16).astype(np.float64)
+    ok = ~np.isnan(half)
+    assert (w[ok].astype(np.float64) == half[ok]).all() and (np.isnan(w) == np.isnan(half)).all()
+    for b in range(256):
+        v = d(b)
+        if np.isfinite(v):
+            assert w[b] == v and (v * 65536) == int(v * 65536)        # integer multiple of 2^-16
+    try:
+        import torch
+        t = torch.arange(256, dtype=torch.uint8).view(torch.float8_e5m2).to(torch.float32).numpy()
+        okt = ~np.isnan(t)
+        assert (t[okt] == w[okt]).all() and (np.isnan(t) == np.isnan(w)).all()
+    except (ImportError, AttributeError, RuntimeError):
+        pass
+
+
+def test_f8e5m2_product_through_the_oracle(oracle):
+    """Widened E5M2 operands through the GEMM oracle: integer-valued codes against int64."""
+    codes = np.array([0x00, 0x3C, 0xBC, 0x40, 0xC0, 0x42, 0xC2, 0x44, 0xC4], np.uint8)      # 0, +-1, +-2, +-3, +-4
+    ints = np.array([0, 1, -1, 2, -2, 3, -3, 4, -4], np.int64)
+    rng = np.random.default_rng(17)
+    ia, ib = rng.integers(0, 9, (13, 40)), rng.integers(0, 9, (40, 7))
+    Aw, Bw = oracle.f8e5m2_widen(codes[ia]), oracle.f8e5m2_widen(codes[ib])
+    ref = oracle.gemm_ref(Aw, 40, Bw, 7, 13, 7, 40)
+    assert (ref == (ints[ia] @ ints[ib])).all()
