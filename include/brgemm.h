@@ -150,6 +150,18 @@ int gemm_f8(int transA, int transB, int64_t M, int64_t N, int64_t K,
             void *workspace, size_t workspace_bytes, void *stream);
 
 /*
+ * The same for the other 8-bit float, OCP E5M2 (1 sign, 5 exponent bits with bias 15, 2
+ * fraction bits; exponent 31 holds the infinities and NaN as in binary16, whose top byte
+ * an E5M2 pattern is; largest finite value 57344).  Section 5(c): one more packed type
+ * through the same kernels - the matrix instruction takes the format as a field.  All
+ * arguments, layout rules and the accuracy note as for gemm_f8.
+ */
+int gemm_bf8(int transA, int transB, int64_t M, int64_t N, int64_t K,
+             const uint8_t *A, int64_t lda, const uint8_t *B, int64_t ldb,
+             float beta, void *C, int64_t ldc, int c_is_f32,
+             void *workspace, size_t workspace_bytes, void *stream);
+
+/*
  * int8 GEMM with exact int32 accumulation (Section 2.2 names INT8 among the packed
  * types; Section 5(c)):  C[M,N] = (accumulate ? C : 0) + A[M,K] x B[K,N].
  * A, B: device, signed 8-bit; C: device, int32; lda/ldb/ldc in elements.  Sums wrap

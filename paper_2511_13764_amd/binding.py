@@ -33,7 +33,7 @@ EXPORTS = ["gemm_f32", "gemm_bf16", "brgemm_bf16", "brgemm_fused", "gemm_workspa
            "gemm_strerror", "gemm_last_hip_error", "gemm_force_variant", "gemm_variant_name",
            "gemm_last_variant", "gemm_last_split", "gemm_mfma_probe", "gemm_pack_vnni_bf16",
            "gemm_packed_b_bytes", "gemm_pack_b_bf16", "gemm_bf16_packed", "gemm_bf16_batched",
-           "gemm_f32_batched", "gemm_f16", "gemm_s8", "gemm_query_plan", "gemm_f8", "gemm_bf16_noalloc"]
+           "gemm_f32_batched", "gemm_f16", "gemm_s8", "gemm_query_plan", "gemm_f8", "gemm_bf16_noalloc", "gemm_bf8"]
 
 _lib = None
 
@@ -65,6 +65,8 @@ def load():
     lib.gemm_f16.argtypes = [ci, ci, i64, i64, i64, vp, i64, vp, i64, cf, vp, i64, ci, vp, sz, vp]
     lib.gemm_f8.restype = ci
     lib.gemm_f8.argtypes = [ci, ci, i64, i64, i64, vp, i64, vp, i64, cf, vp, i64, ci, vp, sz, vp]
+    lib.gemm_bf8.restype = ci
+    lib.gemm_bf8.argtypes = [ci, ci, i64, i64, i64, vp, i64, vp, i64, cf, vp, i64, ci, vp, sz, vp]
     lib.gemm_s8.restype = ci
     lib.gemm_s8.argtypes = [ci, ci, i64, i64, i64, vp, i64, vp, i64, ci, vp, i64, vp]
     lib.brgemm_bf16.restype = ci
@@ -171,6 +173,14 @@ def gemm_f8(transA, transB, M, N, K, A, lda, B, ldb, beta, C, ldc, c_is_f32, wor
     rc = load().gemm_f8(transA, transB, M, N, K, _ptr(A), lda, _ptr(B), ldb, beta, _ptr(C), ldc,
                         int(bool(c_is_f32)), ws, nb, _stream(stream))
     return _check(rc, "gemm_f8", check)
+
+
+def gemm_bf8(transA, transB, M, N, K, A, lda, B, ldb, beta, C, ldc, c_is_f32, workspace=None, stream=None,
+             check=True):
+    ws, nb = _ws(workspace)
+    rc = load().gemm_bf8(transA, transB, M, N, K, _ptr(A), lda, _ptr(B), ldb, beta, _ptr(C), ldc,
+                         int(bool(c_is_f32)), ws, nb, _stream(stream))
+    return _check(rc, "gemm_bf8", check)
 
 
 def gemm_s8(transA, transB, M, N, K, A, lda, B, ldb, accumulate, C, ldc, stream=None, check=True):

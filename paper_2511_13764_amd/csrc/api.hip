@@ -229,6 +229,20 @@ int gemm_f8(int transA, int transB, int64_t M, int64_t N, int64_t K,
     return run(p, workspace, workspace_bytes, false);
 }
 
+int gemm_bf8(int transA, int transB, int64_t M, int64_t N, int64_t K,
+             const uint8_t *A, int64_t lda, const uint8_t *B, int64_t ldb,
+             float beta, void *C, int64_t ldc, int c_is_f32,
+             void *workspace, size_t workspace_bytes, void *stream)
+{
+    Problem p{};
+    p.in_f8 = 1; p.f8_e5m2 = 1; p.transA = transA; p.transB = transB;
+    p.M = M; p.N = N; p.K = K; p.batch = 1;
+    p.A = A; p.lda = lda; p.B = B; p.ldb = ldb;
+    p.beta = beta; p.C = C; p.ldc = ldc; p.c_f32 = c_is_f32 ? 1 : 0;
+    p.stream = (hipStream_t)stream;
+    return run(p, workspace, workspace_bytes, false);
+}
+
 int gemm_s8(int transA, int transB, int64_t M, int64_t N, int64_t K,
             const int8_t *A, int64_t lda, const int8_t *B, int64_t ldb,
             int accumulate, int32_t *C, int64_t ldc, void *stream)

@@ -196,13 +196,13 @@ __device__ __forceinline__ void pp_body(const Bf16Args &p)
     // (B fragment first) so the 16x16 result is C^T: lane l owns row m = l%16 and the 4
     // consecutive columns 4*(l/16) .. +3.
     auto compute_block = [&]() {
-        if constexpr (KIND == KIND_F8) {
+        if constexpr (kind_is_f8(KIND)) {
             // one 128-deep instruction per accumulator: 32 MFMAs, the same pipe time
 #pragma unroll
             for (int a = 0; a < PP_TN; ++a)
 #pragma unroll
                 for (int b = 0; b < PP_TM; ++b)
-                    acc[a][b] = mfma_16x16x128_f8(fb[0][a], fb[1][a], fa[0][b], fa[1][b], acc[a][b]);
+                    acc[a][b] = mfma_16x16x128_f8<KIND>(fb[0][a], fb[1][a], fa[0][b], fa[1][b], acc[a][b]);
             return;
         }
 #pragma unroll
@@ -409,10 +409,10 @@ static hipError_t launch_pp(const Problem &p)
     else if (lay == LAY_MN) kern = bf16_pingpong_kernel<false, LAY_MN, KIND>;          \
     else kern = bf16_pingpong_kernel<false, LAY_PACKED, KIND>;
     if (p.in_s8) kern = bf16_pingpong_kernel<true, LAY_K, KIND_S8>;
-    else if (p.in_f8) kern = bf16_pingpong_kernel<true, LAY_K, KIND_F8>;
+    else if (p.in_f8) kern = p.f8_e5m2 ? bf16_pingpong_kernel<true, LAY_K, KIND_BF8> : bf16_pingpong_kernel<true, LAY_K, KIND_F8>;
     else if (p.in_f16) { BRG_PICK(KIND_F16) } else { BRG_PICK(KIND_BF16) }
 #undef BRG_PICK
-    static thread_local const void *configured[14] = {nullptr};
+    static thread_local const void *configured[16] = {nullptr};
     bool done = false;
     for (const void *c : configured)
         done = done || c == (const void *)kern;

@@ -175,13 +175,13 @@ bf16_stream_kernel(Bf16Args p)
         for (int a = 0; a < TN; ++a)
 #pragma unroll
             for (int b = 0; b < TM; ++b)
-                acc[a][b] = mfma_16x16x32<KIND == KIND_F8 ? KIND_BF16 : KIND>(fb[h][a], fa[h][b], acc[a][b]);
+                acc[a][b] = mfma_16x16x32<kind_is_f8(KIND) ? KIND_BF16 : KIND>(fb[h][a], fa[h][b], acc[a][b]);
     };
     constexpr std::integral_constant<int, 0> H0{};
     constexpr std::integral_constant<int, 1> H1{};
     int rd_slot = 0;
     for (int t = 0; t < n_iter; ++t) {
-        if constexpr (KIND != KIND_F8) {
+        if constexpr (!kind_is_f8(KIND)) {
             if (t > 0)
                 mfma_half(H1);                      // second half of block t - 1
             __builtin_amdgcn_sched_barrier(0);
@@ -207,12 +207,12 @@ bf16_stream_kernel(Bf16Args p)
             for (int i = 0; i < TN; ++i)
                 fb[st][i] = BTile::read_frag16(bt, wn * WN, i, st, lane);
         }
-        if constexpr (KIND == KIND_F8) {
+        if constexpr (kind_is_f8(KIND)) {
 #pragma unroll
             for (int a = 0; a < TN; ++a)
 #pragma unroll
                 for (int b = 0; b < TM; ++b)
-                    acc[a][b] = mfma_16x16x128_f8(fb[0][a], fb[1][a], fa[0][b], fa[1][b], acc[a][b]);
+                    acc[a][b] = mfma_16x16x128_f8<KIND>(fb[0][a], fb[1][a], fa[0][b], fa[1][b], acc[a][b]);
         } else {
             mfma_half(H0);
         }
@@ -221,7 +221,7 @@ bf16_stream_kernel(Bf16Args p)
         wait_lgkmcnt0();
         rd_slot = rd_slot + 1 == stages ? 0 : rd_slot + 1;
     }
-    if constexpr (KIND != KIND_F8) {
+    if constexpr (!kind_is_f8(KIND)) {
         if (n_iter > 0)
             mfma_half(H1);
     }
@@ -287,7 +287,7 @@ __global__ void __launch_bounds__(512)
 bf16_stream128_kernel(Bf16Args p)
 {
     constexpr int BM = 128, NL = 4;              // NL: loader waves
-    static_assert(KIND != KIND_F8, "the 128-deep FP8 instruction takes a whole k-block");
+    static_assert(!kind_is_f8(KIND), "the 128-deep FP8 instruction takes a whole k-block");
     typedef typename TileOf<BM, NL, A_KMAJ ? LAY_K : LAY_MN>::type ATile;
     typedef typename TileOf<ST_BN, NL, B_LAY>::type BTile;
     constexpr int WM = 64, WN = 64, TM = WM / 16, TN = WN / 16;
@@ -486,7 +486,7 @@ hipError_t launch_stream(const Problem &p)
     kern = p.b_packed ? bf16_stream128_kernel<AK, LAY_PACKED, KIND>                            \
            : p.transB == 1 ? bf16_stream128_kernel<AK, LAY_K, KIND> : bf16_stream128_kernel<AK, LAY_MN, KIND>;
         if (p.in_f8) {
-            kern = bf16_stream_kernel<BM, true, LAY_K, KIND_F8>;
+            kern = p.f8_e5m2 ? bf16_stream_kernel<BM, true, LAY_K, KIND_BF8> : bf16_stream_kernel<BM, true, LAY_K, KIND_F8>;
         } else {
             lds = (size_t)S128_STAGES * (BM + ST_BN) * BK * 2;
             if (p.in_s8) {
@@ -507,7 +507,7 @@ hipError_t launch_stream(const Problem &p)
         if (p.in_s8) {
             kern = bf16_stream_kernel<BM, true, LAY_K, KIND_S8>;
         } else if (p.in_f8) {
-            kern = bf16_stream_kernel<BM, true, LAY_K, KIND_F8>;
+            kern = p.f8_e5m2 ? bf16_stream_kernel<BM, true, LAY_K, KIND_BF8> : bf16_stream_kernel<BM, true, LAY_K, KIND_F8>;
         } else if (p.in_f16) {
             BRG_PICK(KIND_F16)
         } else {

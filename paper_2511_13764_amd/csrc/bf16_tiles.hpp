@@ -47,14 +47,17 @@ __device__ __forceinline__ f32x16 mfma_32x32x16(bf16x8 a, bf16x8 b, f32x16 c)
 
 typedef __attribute__((ext_vector_type(8))) int i32x8;
 
-// FP8 (E4M3 x E4M3): v_mfma_f32_16x16x128_f8f6f4 contracts 128 k per instruction, 32
-// bytes per lane and operand, given here as the two 16-byte chunks a lane read.  Which
-// k-bytes sit where inside the 32 is irrelevant as long as both operands agree.
+// FP8 (both operands E4M3, or both E5M2): v_mfma_f32_16x16x128_f8f6f4 contracts 128 k
+// per instruction, 32 bytes per lane and operand, given here as the two 16-byte chunks a
+// lane read.  Which k-bytes sit where inside the 32 is irrelevant as long as both
+// operands agree.  The two format fields of the instruction take 0 for E4M3, 1 for E5M2.
+template <int KIND>
 __device__ __forceinline__ f32x4 mfma_16x16x128_f8(bf16x8 a_lo, bf16x8 a_hi, bf16x8 b_lo, bf16x8 b_hi, f32x4 c)
 {
     const i32x8 a = __builtin_shufflevector(__builtin_bit_cast(i32x4, a_lo), __builtin_bit_cast(i32x4, a_hi), 0, 1, 2, 3, 4, 5, 6, 7);
     const i32x8 b = __builtin_shufflevector(__builtin_bit_cast(i32x4, b_lo), __builtin_bit_cast(i32x4, b_hi), 0, 1, 2, 3, 4, 5, 6, 7);
-    return __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(a, b, c, 0, 0, 0, 0, 0, 0);
+    constexpr int FMT = KIND == KIND_BF8 ? 1 : 0;
+    return __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(a, b, c, FMT, FMT, 0, 0, 0, 0);
 }
 
 #define LDS_AS __attribute__((address_space(3)))

@@ -13,7 +13,8 @@ struct Problem {
     int in_bf16;            // 1: A, B are bf16 bit patterns
     int in_f16;             // 1: A, B are IEEE binary16 bit patterns
     int in_s8;              // 1: A, B are signed 8-bit integers, C is int32
-    int in_f8;              // 1: A, B are FP8 E4M3 patterns (all four 0: fp32)
+    int in_f8;              // 1: A, B are 8-bit floats (all four 0: fp32) ...
+    int f8_e5m2;            // ... of the E5M2 kind (0: E4M3)
     int transA, transB;     // 1: stored transposed (K x M / N x K), row-major
     int64_t M, N, K, batch;
     const void *A;          // base of every A_i
@@ -98,6 +99,11 @@ __device__ __forceinline__ float f8e4m3_to_f32(uint8_t b)
         v = __uint_as_float((uint32_t)(e + 120) << 23 | (uint32_t)f << 20);     // (1 + f/8) * 2^(e-7)
     return (b & 0x80) ? -v : v;
 }
+// FP8 E5M2 (OCP: bias 15, infinities and NaN as in binary16, whose top byte it is).
+__device__ __forceinline__ float f8e5m2_to_f32(uint8_t b)
+{
+    return f16_to_f32((uint16_t)((uint16_t)b << 8));
+}
 // 16-bit C element of either kind.
 __device__ __forceinline__ float c16_to_f32(uint16_t h, int f16) { return f16 ? f16_to_f32(h) : bf16_to_f32(h); }
 __device__ __forceinline__ uint32_t pack_c16x2(float lo, float hi, int f16)
@@ -153,7 +159,8 @@ __device__ __forceinline__ void epilogue_store(const Epilogue &e, float v, int64
 
 inline bool in_16bit(const Problem &p) { return p.in_bf16 || p.in_f16; }
 // Operand kinds as template arguments of the kernels that move 128-byte k-rows.
-constexpr int KIND_BF16 = 0, KIND_F16 = 1, KIND_S8 = 2, KIND_F8 = 3;
+constexpr int KIND_BF16 = 0, KIND_F16 = 1, KIND_S8 = 2, KIND_F8 = 3, KIND_BF8 = 4;      // F8: E4M3, BF8: E5M2
+constexpr bool kind_is_f8(int kind) { return kind == KIND_F8 || kind == KIND_BF8; }
 inline bool in_8bit(const Problem &p) { return p.in_s8 || p.in_f8; }
 
 // ---- launchers (each returns the hipError_t of its launch) -------------------

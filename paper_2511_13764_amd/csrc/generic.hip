@@ -19,7 +19,7 @@ constexpr int GT = 64;      // tile edge (M and N)
 constexpr int GK = 16;      // k-block
 constexpr int GPAD = 1;     // LDS row padding (floats)
 
-// KIND: 0 fp32, 1 bf16, 2 binary16, 3 FP8 E4M3
+// KIND: 0 fp32, 1 bf16, 2 binary16, 3 FP8 E4M3, 4 FP8 E5M2
 template <int KIND>
 __device__ __forceinline__ float load_in(const void *p, int64_t idx)
 {
@@ -29,6 +29,8 @@ __device__ __forceinline__ float load_in(const void *p, int64_t idx)
         return f16_to_f32(((const uint16_t *)p)[idx]);
     if (KIND == 3)
         return f8e4m3_to_f32(((const uint8_t *)p)[idx]);
+    if (KIND == 4)
+        return f8e5m2_to_f32(((const uint8_t *)p)[idx]);
     return ((const float *)p)[idx];
 }
 
@@ -181,6 +183,9 @@ hipError_t launch_generic(const Problem &p)
             hipLaunchKernelGGL(generic_kernel<1>, grid, dim3(256), 0, p.stream, p.transA,
                                p.b_packed ? 2 : p.transB, p.M, p.N, p.K, p.batch, A, p.A_off, p.lda, B, p.B_off,
                                p.ldb, e, p.split, p.partial);
+        else if (p.in_f8 && p.f8_e5m2)
+            hipLaunchKernelGGL(generic_kernel<4>, grid, dim3(256), 0, p.stream, p.transA, p.transB, p.M, p.N,
+                               p.K, p.batch, A, p.A_off, p.lda, B, p.B_off, p.ldb, e, p.split, p.partial);
         else if (p.in_f8)
             hipLaunchKernelGGL(generic_kernel<3>, grid, dim3(256), 0, p.stream, p.transA, p.transB, p.M, p.N,
                                p.K, p.batch, A, p.A_off, p.lda, B, p.B_off, p.ldb, e, p.split, p.partial);
