@@ -297,6 +297,29 @@ int gemm_force_variant(int variant, int split);
 int gemm_query_plan(int dtype, int transA, int transB, int64_t M, int64_t N, int64_t K, int64_t batch,
                     int64_t lda, int64_t ldb, size_t workspace_bytes, int *variant, int *split);
 
+/*
+ * Tile selection by measurement (Section 5(a): the paper picks its tile sizes per target
+ * by sweeping them).  gemm_tune runs C = A x B (beta = 0: C is overwritten with the
+ * product) with every kernel variant and reduction split that accepts the problem, a few
+ * launches each on `stream`, times them with HIP events and remembers the fastest for
+ * this element type (BRGEMM_DTYPE_*), layout, M, N, K, lda, ldb and output type in a
+ * table of the process; every later gemm_f32 / gemm_bf16 / gemm_f16 / brgemm_fused call
+ * with batch == 1 and the same key takes that plan instead of the rule table's (if its
+ * operands meet the plan's alignment rules and its workspace is large enough).
+ * Unlike every other entry point this one WAITS for the device (it synchronises on its
+ * own events, dozens of times) and creates and destroys two events; call it at set-up
+ * time, never under graph capture.  Arguments as in gemm_bf16; variant, split (host,
+ * required) and microseconds (host, may be NULL) receive the winner and its time per
+ * launch.  Returns BRGEMM_OK, BRGEMM_INVALID_ARG (also for empty problems) or
+ * BRGEMM_HIP_ERROR.  gemm_tune_reset forgets every remembered plan.
+ */
+int gemm_tune(int dtype, int transA, int transB, int64_t M, int64_t N, int64_t K,
+              const void *A, int64_t lda, const void *B, int64_t ldb,
+              void *C, int64_t ldc, int c_is_f32,
+              void *workspace, size_t workspace_bytes, void *stream,
+              int *variant, int *split, float *microseconds);
+void gemm_tune_reset(void);
+
 /* Name of variant number v ("" past the end): lets a harness enumerate them. */
 const char *gemm_variant_name(int v);
 

@@ -33,7 +33,7 @@ EXPORTS = ["gemm_f32", "gemm_bf16", "brgemm_bf16", "brgemm_fused", "gemm_workspa
            "gemm_strerror", "gemm_last_hip_error", "gemm_force_variant", "gemm_variant_name",
            "gemm_last_variant", "gemm_last_split", "gemm_mfma_probe", "gemm_pack_vnni_bf16",
            "gemm_packed_b_bytes", "gemm_pack_b_bf16", "gemm_bf16_packed", "gemm_bf16_batched",
-           "gemm_f32_batched", "gemm_f16", "gemm_s8", "gemm_query_plan", "gemm_f8", "gemm_bf16_noalloc", "gemm_bf8"]
+           "gemm_f32_batched", "gemm_f16", "gemm_s8", "gemm_query_plan", "gemm_f8", "gemm_bf16_noalloc", "gemm_bf8", "gemm_tune", "gemm_tune_reset"]
 
 _lib = None
 
@@ -103,6 +103,11 @@ def load():
     lib.gemm_query_plan.restype = ci
     lib.gemm_query_plan.argtypes = [ci, ci, ci, i64, i64, i64, i64, i64, i64, sz, ctypes.POINTER(ci),
                                     ctypes.POINTER(ci)]
+    lib.gemm_tune.restype = ci
+    lib.gemm_tune.argtypes = [ci, ci, ci, i64, i64, i64, vp, i64, vp, i64, vp, i64, ci, vp, sz, vp,
+                              ctypes.POINTER(ci), ctypes.POINTER(ci), ctypes.POINTER(ctypes.c_float)]
+    lib.gemm_tune_reset.restype = None
+    lib.gemm_tune_reset.argtypes = []
     lib.gemm_mfma_probe.restype = ci
     lib.gemm_mfma_probe.argtypes = [ci, vp, i64, ci, vp, ctypes.POINTER(ctypes.c_double), vp]
     _lib = lib
@@ -254,6 +259,25 @@ def gemm_query_plan(dtype, transA, transB, M, N, K, batch=1, lda=None, ldb=None,
     if rc != OK:
         raise BrgemmError(rc, "gemm_query_plan")
     return gemm_variant_name(v.value), s.value
+
+
+def gemm_tune(dtype, transA, transB, M, N, K, A, lda, B, ldb, C, ldc, c_is_f32, workspace=None, stream=None,
+              check=True):
+    """Returns (variant name, split, microseconds per launch) of the fastest plan, which later calls
+    of the same shape then take.  Waits for the device.  With check=False: the return code."""
+    ws, nb = _ws(workspace)
+    v, sp, us = ctypes.c_int(-1), ctypes.c_int(0), ctypes.c_float(0.0)
+    rc = load().gemm_tune(dtype, transA, transB, M, N, K, _ptr(A), lda, _ptr(B), ldb, _ptr(C), ldc,
+                          int(bool(c_is_f32)), ws, nb, _stream(stream), ctypes.byref(v), ctypes.byref(sp),
+                          ctypes.byref(us))
+    if not check:
+        return rc
+    _check(rc, "gemm_tune", True)
+    return gemm_variant_name(v.value), sp.value, us.value
+
+
+def gemm_tune_reset():
+    load().gemm_tune_reset()
 
 
 def gemm_mfma_probe(dtype, operands, iters, blocks, sink, stream=None, check=True):

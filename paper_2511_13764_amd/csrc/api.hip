@@ -4,7 +4,9 @@
 #include "../../include/brgemm.h"
 #include "common.hpp"
 #include "variants.hpp"
+#include <map>
 #include <mutex>
+#include <tuple>
 
 using namespace brg;
 
@@ -100,6 +102,38 @@ int scratch_of_current_device(void **out)
     return BRGEMM_OK;
 }
 
+// Plans found by measurement (gemm_tune): shape -> (variant, split), consulted by every
+// later call of the same element type, layout, sizes and leading dimensions.
+typedef std::tuple<int, int, int, int, int, int64_t, int64_t, int64_t, int64_t, int64_t, int64_t> TuneKey;
+std::mutex tune_mutex;
+std::map<TuneKey, Plan> tune_table;
+
+TuneKey tune_key(const Problem &p)
+{
+    const int dtype = p.in_bf16 ? 1 : p.in_f16 ? 2 : p.in_s8 ? 3 : p.in_f8 ? (p.f8_e5m2 ? 5 : 4) : 0;
+    return TuneKey(dtype, p.transA, p.transB, p.c_f32, p.b_packed, p.M, p.N, p.K, p.batch, p.lda, p.ldb);
+}
+
+bool tuned_plan(const Problem &p, size_t workspace_bytes, Plan *out)
+{
+    if (p.nmat != 1 || p.A_off)
+        return false;
+    Plan plan;
+    {
+        std::lock_guard<std::mutex> lock(tune_mutex);
+        auto it = tune_table.find(tune_key(p));
+        if (it == tune_table.end())
+            return false;
+        plan = it->second;
+    }
+    // the entry was measured on aligned operands with enough workspace: check this call's
+    Plan checked;
+    if (choose_plan(p, workspace_bytes, plan.variant, plan.split, &checked) != BRGEMM_OK)
+        return false;
+    *out = checked;
+    return true;
+}
+
 // preset: a plan the caller has already chosen for this problem (nullptr: choose here).
 int run(Problem &p, void *workspace, size_t workspace_bytes, bool need_offsets, const Plan *preset = nullptr)
 {
@@ -121,7 +155,7 @@ int run(Problem &p, void *workspace, size_t workspace_bytes, bool need_offsets, 
     Plan plan;
     if (preset)
         plan = *preset;
-    else
+    else if (tl_forced_variant >= 0 || tl_forced_split > 0 || !tuned_plan(p, workspace_bytes, &plan))
         rc = choose_plan(p, workspace_bytes, tl_forced_variant, tl_forced_split, &plan);
     if (rc != BRGEMM_OK)
         return rc;
@@ -404,6 +438,98 @@ int gemm_f32_batched(int transA, int transB, int64_t M, int64_t N, int64_t K, in
     p.beta = beta; p.C = C; p.ldc = ldc; p.c_f32 = 1;
     p.stream = (hipStream_t)stream;
     return run_batched(p, nmat, strideA, strideB, strideC);
+}
+
+int gemm_tune(int dtype, int transA, int transB, int64_t M, int64_t N, int64_t K,
+              const void *A, int64_t lda, const void *B, int64_t ldb,
+              void *C, int64_t ldc, int c_is_f32,
+              void *workspace, size_t workspace_bytes, void *stream,
+              int *variant, int *split, float *microseconds)
+{
+    if (dtype != BRGEMM_DTYPE_F32 && dtype != BRGEMM_DTYPE_BF16 && dtype != BRGEMM_DTYPE_F16)
+        return BRGEMM_INVALID_ARG;
+    if (!variant || !split || M <= 0 || N <= 0 || K <= 0)
+        return BRGEMM_INVALID_ARG;
+    if (dtype == BRGEMM_DTYPE_F32 && !c_is_f32)
+        return BRGEMM_INVALID_ARG;
+    Problem p{};
+    p.in_bf16 = dtype == BRGEMM_DTYPE_BF16; p.in_f16 = dtype == BRGEMM_DTYPE_F16;
+    p.transA = transA; p.transB = transB;
+    p.M = M; p.N = N; p.K = K; p.batch = 1; p.nmat = 1;
+    p.A = A; p.lda = lda; p.B = B; p.ldb = ldb;
+    p.beta = 0.0f; p.C = C; p.ldc = ldc; p.c_f32 = c_is_f32 ? 1 : 0;
+    p.stream = (hipStream_t)stream;
+    int rc = validate(p, workspace, workspace_bytes, false);
+    if (rc != BRGEMM_OK)
+        return rc;
+
+    hipEvent_t e0 = nullptr, e1 = nullptr;
+    hipError_t he = hipEventCreate(&e0);
+    if (he == hipSuccess)
+        he = hipEventCreate(&e1);
+    Plan best{V_GENERIC, 1};
+    float best_us = -1.0f;
+    static const int splits[] = {1, 2, 3, 4, 5, 6, 7, 8, 10, 12, 16};
+    for (int v = V_COUNT - 1; v >= 0 && he == hipSuccess; --v) {
+        if (v == V_GENERIC && best_us >= 0.0f)
+            break;                                  // the general kernel only when nothing else takes the problem
+        for (int s : splits) {
+            Plan plan;
+            if (choose_plan(p, workspace_bytes, v, s, &plan) != BRGEMM_OK)
+                continue;
+            const int64_t kblocks = K / 64;
+            if (s > 1 && kblocks / s < 2)
+                continue;
+            // two untimed launches, then as many as fill about 300 us (at least 3)
+            int reps = 3;
+            for (int pass = 0; pass < 2 && he == hipSuccess; ++pass) {
+                const int n = pass == 0 ? 2 : reps;
+                he = hipEventRecord(e0, p.stream);
+                for (int i = 0; i < n && he == hipSuccess; ++i) {
+                    Problem q = p;
+                    rc = run(q, workspace, workspace_bytes, false, &plan);
+                    if (rc != BRGEMM_OK)
+                        he = hipErrorLaunchFailure;
+                }
+                if (he == hipSuccess)
+                    he = hipEventRecord(e1, p.stream);
+                if (he == hipSuccess)
+                    he = hipEventSynchronize(e1);
+                float ms = 0.0f;
+                if (he == hipSuccess)
+                    he = hipEventElapsedTime(&ms, e0, e1);
+                const float us = ms * 1000.0f / (float)n;
+                if (pass == 0) {
+                    reps = us > 0.0f ? (int)(300.0f / us) : 3;
+                    reps = reps < 3 ? 3 : reps > 50 ? 50 : reps;
+                } else if (he == hipSuccess && (best_us < 0.0f || us < best_us)) {
+                    best_us = us;
+                    best = plan;
+                }
+            }
+        }
+    }
+    if (e0) (void)hipEventDestroy(e0);
+    if (e1) (void)hipEventDestroy(e1);
+    if (he != hipSuccess || best_us < 0.0f) {
+        tl_last_hip_error = (int)he;
+        return BRGEMM_HIP_ERROR;
+    }
+    {
+        std::lock_guard<std::mutex> lock(tune_mutex);
+        tune_table[tune_key(p)] = best;
+    }
+    *variant = best.variant;
+    *split = best.split;
+    if (microseconds)
+        *microseconds = best_us;
+    return BRGEMM_OK;
+}
+
+void gemm_tune_reset(void)
+{
+    std::lock_guard<std::mutex> lock(tune_mutex);
+    tune_table.clear();
 }
 
 size_t gemm_workspace_bytes(int dtype, int64_t M, int64_t N, int64_t K, int64_t batch)

@@ -233,3 +233,20 @@ def test_f8_argument_rules(lib):
     assert call(M=0) == B.OK and call(N=0) == B.OK
     for kw in (dict(M=-1), dict(K=-1), dict(tB=2), dict(lda=127), dict(ldb=127), dict(ldc=7), dict(B=0), dict(C=0)):
         assert call(**kw) == B.INVALID_ARG, kw
+
+
+def test_tune_rejects_bad_arguments_before_any_device_work(lib):
+    import ctypes
+    v, sp = ctypes.c_int(0), ctypes.c_int(0)
+    ok = [B.DTYPE_BF16, 0, 0, 64, 64, 64, P, 64, P, 64, P, 64, 0, None, 0, None, ctypes.byref(v), ctypes.byref(sp), None]
+    for pos, bad in ((0, 9), (1, 2), (3, 0), (4, -1), (5, 0), (7, 8), (9, 8), (11, 8), (6, None), (10, None)):
+        a = list(ok)
+        a[pos] = bad
+        assert lib.gemm_tune(*a) == B.INVALID_ARG, pos
+    a = list(ok)
+    a[16] = None                                         # nowhere to put the answer
+    assert lib.gemm_tune(*a) == B.INVALID_ARG
+    a = list(ok)
+    a[0], a[12] = B.DTYPE_F32, 0                         # fp32 operands need an fp32 C
+    assert lib.gemm_tune(*a) == B.INVALID_ARG
+    lib.gemm_tune_reset()
