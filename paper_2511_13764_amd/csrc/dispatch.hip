@@ -114,9 +114,16 @@ static void plan_small_grid(const Problem &p, size_t workspace_bytes, bool may_s
     double best_t = 1e30;
     *bm_out = 128;
     *split_out = 1;
+    // A B operand far larger than the L2s (4 MiB per XCD) is streamed, and every further
+    // row of tiles streams it again: then only the tallest tile is considered (measured:
+    // 256 x 4096 x 4096 takes 19.0 us as 128-row tiles with split 3 and 24.6 us as 32-row
+    // tiles; 1024 x 2048 x 8192 39.8 against 48.9 us with 64-row tiles).
+    const bool b_streams = (double)p.N * (double)p.K * (double)p.batch * 2.0 > 8.0 * 1024 * 1024 && p.M > 128;
     for (int i = 0; i < 3; ++i) {
         const int bm = heights[i];
         if (!bf16_stream_eligible(p, bm) || (bm < 128 && p.in_f8))
+            continue;
+        if (bm < 128 && b_streams && bf16_stream_eligible(p, 128))
             continue;
         const int64_t tiles = ((p.M + bm - 1) / bm) * ((p.N + 127) / 128) * p.nmat;
         if (bm < 128 && tiles > 256)
@@ -144,6 +151,37 @@ static void plan_small_grid(const Problem &p, size_t workspace_bytes, bool may_s
 // MLP shape): one workgroup per CU works through a 128x128x32 k-block in ~2.0 us
 // (the fp32 MFMA rate), a launch costs ~8 us of latency, and the reduction adds a
 // second launch plus split*M*N*8 bytes at ~3 TB/s.
+// Between 257 and 512 tiles of 128 x 128: either the two-stage 128 x 128 kernel with two
+// workgroups per CU (about 1.0 us per k-block when all 512 are there) or the 256 x 256
+// kernel on a quarter as many tiles with the reduction split so that they fill the chip
+// (1.22 us per k-block, plus the partial tiles: split * M * N * 4 bytes read and the
+// result written at ~5 TB/s, plus a second launch).  Measured: 2048 x 4096 x 11008 takes
+// 174 us the first way and 144 us the second (split 2), 1024 x 8192 x 8192 131 against
+// 113 us; at K = 4096 the two are level.  Returns the split for the 256 x 256 kernel, or 0
+// to stay with the 128 x 128 kernel.
+static int split_for_mid_grid(const Problem &p, size_t workspace_bytes)
+{
+    if (!bf16_pingpong_eligible(p))
+        return 0;
+    const double kblocks = (double)p.batch * (double)(p.K / 64);
+    const int64_t pp_tiles = ((p.M + 255) / 256) * ((p.N + 255) / 256);
+    const double t_128 = 3.0 + kblocks * 1.0;
+    int best = 0;
+    double best_t = t_128 * 0.92;                   // switch only for a clear gain
+    for (int s = 2; s <= kMaxSplit; ++s) {
+        if (pp_tiles * s > 256 || kblocks / s < 16.0 || split_bytes(p, s) > workspace_bytes)
+            continue;
+        const double per = (double)(int64_t)((kblocks + s - 1) / s);
+        const double mn = (double)p.M * (double)p.N;
+        const double t = 12.0 + per * 1.22 + 4.0 + (s * mn * 4.0 + mn * 2.0) / 5.0e6;
+        if (t < best_t) {
+            best_t = t;
+            best = s;
+        }
+    }
+    return best;
+}
+
 static int split_for_f32(const Problem &p, size_t workspace_bytes)
 {
     const int64_t tiles = ((p.M + 127) / 128) * ((p.N + 127) / 128);
@@ -191,8 +229,14 @@ int choose_plan(const Problem &p, size_t workspace_bytes, int forced_variant, in
                 plan.variant = bm == 32 ? V_BF16_STREAM32 : bm == 64 ? V_BF16_STREAM64 : V_BF16_STREAM128;
                 plan.split = split;
             } else {
-                plan.variant = (p.in_f8 && bf16_stream_eligible(p, 128)) ? V_BF16_STREAM128 : V_BF16_128x128;
-                plan.split = single ? split_for_small_grid(p, workspace_bytes) : 1;
+                const int pp_split = (single && !p.in_f8) ? split_for_mid_grid(p, workspace_bytes) : 0;
+                if (pp_split > 0) {
+                    plan.variant = V_BF16_PP256;
+                    plan.split = pp_split;
+                } else {
+                    plan.variant = (p.in_f8 && bf16_stream_eligible(p, 128)) ? V_BF16_STREAM128 : V_BF16_128x128;
+                    plan.split = single ? split_for_small_grid(p, workspace_bytes) : 1;
+                }
             }
         }
     }

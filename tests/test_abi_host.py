@@ -207,6 +207,14 @@ def test_shape_to_tile_table(lib):
     assert q(BF, 0, 0, 2304, 2304, 2304) == ("bf16_128x128x64", 1)
     assert q(BF, 0, 0, 2816, 2816, 2816) == ("bf16_128x128x64", 1)
     assert q(BF, 0, 0, 3072, 3072, 3072) == ("bf16_pingpong_256x256x64", 1)
+    # 257..512 tiles with a long reduction: 256x256 tiles with the reduction split to fill the chip
+    assert q(BF, 0, 1, 2048, 4096, 11008) == ("bf16_pingpong_256x256x64", 2)
+    assert q(BF, 0, 1, 1024, 8192, 8192) == ("bf16_pingpong_256x256x64", 2)
+    assert q(BF, 0, 1, 2048, 4096, 4096) == ("bf16_128x128x64", 1)              # short reduction: level, stays
+    assert q(BF, 0, 1, 2048, 4096, 11008, workspace_bytes=0) == ("bf16_128x128x64", 1)
+    # a B operand that streams (far larger than the L2s): only 128-row tiles
+    assert q(BF, 0, 1, 256, 4096, 4096)[0] == "bf16_stream_128x128x64"
+    assert q(BF, 0, 1, 1024, 2048, 8192) == ("bf16_stream_128x128x64", 2)
     # batch-reduce into a small C: split over the flattened (batch, k) range
     assert q(BF, 0, 0, 512, 512, 64, batch=64, lda=64, ldb=512) == ("bf16_stream_32x128x64", 8)
     # fp32: one kernel, split by the time model
