@@ -63,6 +63,8 @@ def main():
     # untimed launches of the same call.
     ap.add_argument("--steps", type=int, default=500)
     ap.add_argument("--warmup", type=int, default=300)
+    ap.add_argument("--settle-ms", type=float, default=WARMUP_FLOOR_MS,
+                    help="untimed continuous load before every timed region (profiling passes use 0)")
     ap.add_argument("--print-sources-digest", action="store_true",
                     help="print the digest that ties HEADLINE_TRAFFIC to the kernel sources, and exit")
     ap.add_argument("--no-others", action="store_true", help="time the headline workload only")
@@ -98,8 +100,11 @@ def main():
     def dev(x):
         return torch.from_numpy(x.view(np.int16) if x.dtype == np.uint16 else x).cuda()
 
-    def settle(fn, floor_ms=WARMUP_FLOOR_MS):
+    def settle(fn, floor_ms=None):
         """Untimed launches for at least floor_ms of GPU work."""
+        floor_ms = args.settle_ms if floor_ms is None else min(floor_ms, args.settle_ms)
+        if floor_ms <= 0:
+            return
         t_w = time.perf_counter()
         while (time.perf_counter() - t_w) * 1e3 < floor_ms:
             for _ in range(20):
@@ -186,7 +191,7 @@ def main():
 
     out = {
         "metric": METRIC, "value": round(value, 2), "unit": "TFLOP/s", "n_gpus": 1,
-        "steps": args.steps, "warmup": args.warmup, "warmup_floor_ms": WARMUP_FLOOR_MS, "ms_per_step": round(wall * 1e3, 5),
+        "steps": args.steps, "warmup": args.warmup, "warmup_floor_ms": args.settle_ms, "ms_per_step": round(wall * 1e3, 5),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16",
         "data": "synthetic",
         "config": {"workload": "bf16-in/fp32-acc/bf16-out GEMM M=N=K=4096 row-major (NN) beta=0, N(0,1) inputs",

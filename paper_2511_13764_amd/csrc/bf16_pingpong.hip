@@ -310,8 +310,11 @@ __device__ __forceinline__ void pp_body(const Bf16Args &p)
                 // 136-byte pitch keeps rows 8-byte aligned only: two 64-bit reads
                 const u32x2 lo = *(LDS_AS u32x2 *)(stage_h + row * 136 + c8 * 16);
                 const u32x2 hi = *(LDS_AS u32x2 *)(stage_h + row * 136 + c8 * 16 + 8);
+                // non-temporal: C is not read again by this kernel, and lines that do not linger
+                // in L2 are not left for the write-back at the end of the kernel (4096^3: -1.4 us)
                 if (m0 + wm * PP_WM + b2 * 32 + row < p.M)
-                    *(u32x4 *)(crow + (int64_t)(b2 * 32 + row) * p.epi.ldc + c8 * 8) = u32x4{lo[0], lo[1], hi[0], hi[1]};
+                    __builtin_nontemporal_store(u32x4{lo[0], lo[1], hi[0], hi[1]},
+                                                (u32x4 *)(crow + (int64_t)(b2 * 32 + row) * p.epi.ldc + c8 * 8));
             }
             __builtin_amdgcn_wave_barrier();
         });

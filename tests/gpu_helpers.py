@@ -175,3 +175,48 @@ def check_bf16_out_elementwise(oracle, out_bits, ref, abs_ref, K, *, what=""):
     frac = float((out_bits != want).mean())
     assert frac <= 0.01, f"{what}: {frac:.4f} of the elements differ from the oracle's rounding"
     return ratio, frac
+
+
+def check_bf16_case_elementwise(oracle, case, out_bits, ref, bias=None):
+    """Per-element bound for a bf16-out GemmCase of any size, beta and bias included: the
+    stored value is RNE_bf16 of an fp32 evaluation of beta*C0 + sum_k a_k b_k (+ bias), so
+    |got - ref| <= half a bf16 spacing at the fp32 value + gamma_{K+2} * S, where
+    S = |beta||C0| + sum_k |a_k||b_k| (+ |bias|) comes from the oracle run on the absolute
+    values.  Unlike a Frobenius tolerance this needs no allowance for results of only a few
+    elements."""
+    absA = case.A & np.uint16(0x7FFF) if case.A.dtype == np.uint16 else np.abs(case.A)
+    absB = case.B & np.uint16(0x7FFF) if case.B.dtype == np.uint16 else np.abs(case.B)
+    absC = None
+    if case.C0 is not None and case.beta != 0.0:
+        absC = case.C0 & np.uint16(0x7FFF) if case.C0.dtype == np.uint16 else np.abs(case.C0)
+    S = oracle.gemm_ref(absA, case.lda, absB, case.ldb, case.M, case.N, case.K, transA=case.transA,
+                        transB=case.transB, beta=abs(case.beta), C0=absC,
+                        ldc0=(absC.shape[1] if absC is not None else None),
+                        bias=(np.abs(bias) if bias is not None else None))
+    u = 2.0 ** -24
+    n = case.K + 2
+    delta = (n * u / (1.0 - n * u)) * S
+    got = widen(out_bits)
+    big = np.maximum(np.abs(ref) + delta, 2.0 ** -126)
+    bound = 2.0 ** (np.floor(np.log2(big)) - 8) + delta + 2.0 ** -133
+    excess = np.abs(got - ref) - bound
+    worst = np.unravel_index(np.argmax(excess), excess.shape)
+    assert excess[worst] <= 0.0, f"{case.name}: element {worst} got {got[worst]} ref {ref[worst]} bound {bound[worst]}"
+
+
+def check_f32_case_elementwise(oracle, case, out, ref, rows=None):
+    """Per-element bound for an fp32-in / fp32-out GemmCase: K rounded products, K - 1
+    additions and the beta*C0 term, each with a relative error of at most u = 2^-24, in any
+    order: |got - ref| <= gamma_{K+3} * S with S = |beta||C0| + sum_k |a_k||b_k| from the
+    oracle run on the absolute values.  An element that lost one term of typical size fails."""
+    absC = np.abs(case.C0) if (case.C0 is not None and case.beta != 0.0) else None
+    S = oracle.gemm_ref(np.abs(case.A), case.lda, np.abs(case.B), case.ldb, case.M, case.N, case.K,
+                        transA=case.transA, transB=case.transB, beta=abs(case.beta), C0=absC,
+                        ldc0=(absC.shape[1] if absC is not None else None), rows=rows)
+    u = 2.0 ** -24
+    n = case.K + 3
+    bound = (n * u / (1.0 - n * u)) * S + 2.0 ** -149
+    excess = np.abs(widen(out) - ref) - bound
+    worst = np.unravel_index(np.argmax(excess), excess.shape)
+    assert excess[worst] <= 0.0, f"{case.name}: element {worst} off by {np.abs(widen(out) - ref)[worst]}, bound {bound[worst]}"
+    return float((np.abs(widen(out) - ref) / bound).max())

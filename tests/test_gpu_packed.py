@@ -134,9 +134,12 @@ def test_packed_gemm_ragged(oracle, M, N, K, tA, tB):
     ws = B.gemm_workspace_bytes(1, M, N, K)
     out, used, split = run_packed(case, workspace_bytes=ws, ldc=N + 8)
     assert np.isfinite(H.widen(out)).all(), "padding (NaN) leaked into the result"
-    err = H.rel_fro(H.widen(out), ref)
-    # a bf16 C of very few elements can exceed the tolerance by rounding alone
-    assert err <= (H.TOL_BF16 if M * N >= 4096 else 4e-3), (used, split, err)
+    # every element within one bf16 rounding of an fp32 evaluation; the Frobenius limit (an RMS
+    # figure) only where there are enough elements for it to mean something
+    H.check_bf16_case_elementwise(oracle, case, out, ref)
+    if M * N >= 4096:
+        err = H.rel_fro(H.widen(out), ref)
+        assert err <= H.TOL_BF16, (used, split, err)
 
 
 def test_packed_gemm_fused_bias_relu_matches_flat(oracle):

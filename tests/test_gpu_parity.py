@@ -30,6 +30,10 @@ def _need_gpu():
     B.load()
 
 
+def _abs_bits(x):
+    return x & np.uint16(0x7FFF)
+
+
 def _tol(case):
     if case.dtype == "f32":
         return H.TOL_F32
@@ -54,7 +58,8 @@ def test_config2_f32_2048_beta(oracle):
     out, _ = H.run_gemm_case(case, workspace_bytes=B.gemm_workspace_bytes(0, case.M, case.N, case.K))
     ref = H.oracle_gemm_case(oracle, case)
     err = H.rel_fro(H.widen(out), ref)
-    say(f"{case.name} rel_fro={err:.3e}")
+    worst = H.check_f32_case_elementwise(oracle, case, out, ref)
+    say(f"{case.name} rel_fro={err:.3e}, every element within {worst:.3f} of the fp32 summation bound")
     assert err <= H.TOL_F32
 
 
@@ -69,6 +74,7 @@ def test_f32_4096_sampled(oracle):
     rows = H.sample_rows(4096, 64, tile=128)
     ref = H.oracle_gemm_case(oracle, case, rows=rows)
     err = H.rel_fro(H.widen(out[rows]), ref)
+    H.check_f32_case_elementwise(oracle, case, out[rows], ref, rows=rows)
     say(f"{case.name} rows={len(rows)} rel_fro={err:.3e}")
     assert err <= H.TOL_F32
 
@@ -85,6 +91,8 @@ def test_config3_bf16_square_full(oracle, size):
     say(f"{case.name} rel_fro={err:.3e} vs_rounded_oracle={err_out:.3e}")
     assert err <= H.TOL_BF16
     assert err_out <= 1e-3
+    abs_ref = oracle.gemm_ref(_abs_bits(case.A), case.lda, _abs_bits(case.B), case.ldb, size, size, size)
+    H.check_bf16_out_elementwise(oracle, out, ref, abs_ref, size, what=case.name)
     # fp32-out variant of the same problem
     case.c_is_f32 = True
     out32, _ = H.run_gemm_case(case)
@@ -110,10 +118,6 @@ def test_config3_bf16_square_sampled(oracle, size):
     errc = H.rel_fro(H.widen(out[:, cols]).T, refT)
     say(f"{case.name} cols={len(cols)} rel_fro={errc:.3e}")
     assert errc <= H.TOL_BF16
-
-
-def _abs_bits(x):
-    return x & np.uint16(0x7FFF)
 
 
 @pytest.mark.parametrize("which", ["square4096", "mlp_up4096"])
@@ -610,8 +614,14 @@ def test_seeded_random_shape_sweep(oracle):
         ref = H.oracle_gemm_case(oracle, case)
         got = H.widen(out)
         assert np.isfinite(got).all(), case.name
-        tol = 1e-5 if c_f32 else (H.TOL_BF16 if M * N >= 4096 else 4e-3)
-        assert H.rel_fro(got, ref) <= tol, (case.name, B.gemm_variant_name(B.gemm_last_variant()))
+        if c_f32:
+            assert H.rel_fro(got, ref) <= 1e-5, (case.name, B.gemm_variant_name(B.gemm_last_variant()))
+        else:
+            # every element within one bf16 rounding of an fp32 evaluation; the Frobenius limit
+            # (an RMS figure) only where there are enough elements for it to mean something
+            H.check_bf16_case_elementwise(oracle, case, out, ref)
+            if M * N >= 4096:
+                assert H.rel_fro(got, ref) <= H.TOL_BF16, (case.name, B.gemm_variant_name(B.gemm_last_variant()))
     assert len(seen) >= 5, seen
 
 
