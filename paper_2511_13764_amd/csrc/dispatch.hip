@@ -104,7 +104,8 @@ static int split_for_stream(const Problem &p, int bm, size_t workspace_bytes)
 // the 32- and 64-row kernels share a CU.  Time model in microseconds, constants from
 // sweeps over 512^3 ... 2048^3, 512 x 512 x 4096 and the scattered batch-reduce
 // configuration: a k-block costs a workgroup 0.20 / 0.29 / 0.42 us at 32 / 64 / 128 rows
-// (twice that when every block starts with a tile offset fetched from memory), a split
+// (twice that for a batch-reduce over scattered tiles, where every 64-deep block is a new tile
+// somewhere else in memory), a split
 // costs a second launch (4.5 us) plus writing and reading its partial tiles.
 static void plan_small_grid(const Problem &p, size_t workspace_bytes, bool may_split, int *bm_out, int *split_out)
 {
