@@ -78,8 +78,13 @@ bf16_mfma_kernel(Bf16Args p)
     // operand pointers that go with it.  Advanced without divisions.
     int ld_i = n_iter > 0 ? it_begin / kblocks : 0;
     int ld_kb = n_iter > 0 ? it_begin - ld_i * kblocks : 0;
-    const uint16_t *ld_a = uniform_ptr(p.A + (p.A_off ? p.A_off[ld_i] : 0) + a_origin + ld_kb * a_kstep);
-    const uint16_t *ld_b = uniform_ptr(p.B + (p.B_off ? p.B_off[ld_i] : 0) + b_origin + ld_kb * b_kstep);
+    TileOffsets offs_a, offs_b;                 // this wave's window of the tile offsets
+    if (p.A_off) {
+        offs_a.init(p.A_off, p.batch, ld_i, lane);
+        offs_b.init(p.B_off, p.batch, ld_i, lane);
+    }
+    const uint16_t *ld_a = uniform_ptr(p.A + (p.A_off ? offs_a.get(ld_i, lane) : 0) + a_origin + ld_kb * a_kstep);
+    const uint16_t *ld_b = uniform_ptr(p.B + (p.B_off ? offs_b.get(ld_i, lane) : 0) + b_origin + ld_kb * b_kstep);
     // Tile offsets live in device memory, so their alignment cannot be checked on the
     // host: if any A_off / B_off is not a multiple of 8 elements (16 bytes) the whole
     // workgroup stages its blocks through registers with 2-byte loads instead.
@@ -120,8 +125,8 @@ bf16_mfma_kernel(Bf16Args p)
             ld_kb = 0;
             ++ld_i;
             if (p.A_off && ld_i < (int)p.batch) {
-                ld_a = uniform_ptr(p.A + p.A_off[ld_i] + a_origin);
-                ld_b = uniform_ptr(p.B + p.B_off[ld_i] + b_origin);
+                ld_a = uniform_ptr(p.A + offs_a.get(ld_i, lane) + a_origin);
+                ld_b = uniform_ptr(p.B + offs_b.get(ld_i, lane) + b_origin);
             }
         } else {
             ld_a += a_kstep;

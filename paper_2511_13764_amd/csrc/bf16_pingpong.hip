@@ -53,7 +53,9 @@ __device__ __forceinline__ void phase_sync()
 // offsets that are not 16-byte aligned).  EDGE: the tile overhangs the matrix in the
 // direction this wave loads, so lanes outside it are switched off.  Both are uniform
 // over the workgroup / wave and chosen once, so the loop body carries no branches for them.
-template <bool A_KMAJ, int B_LAY, bool DIRECT, bool EDGE, int KIND>
+// HAS_OFF: a batch-reduce call with tile offsets.  A template argument so that the plain GEMM
+// body carries none of the offset state (the kernel sits at 251-255 of 256 registers).
+template <bool A_KMAJ, int B_LAY, bool DIRECT, bool EDGE, int KIND, bool HAS_OFF>
 __device__ __forceinline__ void pp_body(const Bf16Args &p)
 {
     // Load duty: waves 0-3 fetch the B halves, waves 4-7 the A halves (8 wave-loads
@@ -109,7 +111,16 @@ __device__ __forceinline__ void pp_body(const Bf16Args &p)
     // source pointer and its ring slot.  Half-block 2t is A(t), 2t+1 is B(t); slot = index % 5.
     int ld_i = n_iter > 0 ? it_begin / kblocks : 0;
     int ld_kb = n_iter > 0 ? it_begin - ld_i * kblocks : 0;
-    const uint16_t *ld_ptr = uniform_ptr(op_base + (op_off ? op_off[ld_i] : 0) + op_origin + ld_kb * op_kstep);
+    // Tile offsets of a batch-reduce call: this wave's operand only, 64 at a time in two
+    // registers (see TileOffsets: fetched one by one they would sit, as dependent vector
+    // loads, in front of every tile's loads and drain the loads in flight).
+    TileOffsets offs;
+    if constexpr (HAS_OFF)
+        offs.init(op_off, p.batch, ld_i, lane);
+    int64_t first_off = 0;
+    if constexpr (HAS_OFF)
+        first_off = offs.get(ld_i, lane);
+    const uint16_t *ld_ptr = uniform_ptr(op_base + first_off + op_origin + ld_kb * op_kstep);
     int ld_slot = group ? 0 : 1;
 
     // One of the 8 wave-loads of this wave's next half-block.
@@ -139,8 +150,10 @@ __device__ __forceinline__ void pp_body(const Bf16Args &p)
         if (++ld_kb == kblocks) {
             ld_kb = 0;
             ++ld_i;
-            if (op_off && ld_i < (int)p.batch)
-                ld_ptr = uniform_ptr(op_base + op_off[ld_i] + op_origin);
+            if constexpr (HAS_OFF) {
+                if (ld_i < (int)p.batch)
+                    ld_ptr = uniform_ptr(op_base + offs.get(ld_i, lane) + op_origin);
+            }
         } else {
             ld_ptr += op_kstep;
         }
@@ -348,7 +361,9 @@ __device__ __forceinline__ void pp_body(const Bf16Args &p)
     });
 }
 
-template <bool A_KMAJ, int B_LAY, int KIND>
+// HAS_OFF: the batch-reduce form (tile offsets in device memory) is a kernel of its own, so
+// that the plain GEMM kernel carries none of its state or code.
+template <bool A_KMAJ, int B_LAY, int KIND, bool HAS_OFF>
 __global__ void __launch_bounds__(512)
 bf16_pingpong_kernel(Bf16Args p)
 {
@@ -363,7 +378,7 @@ bf16_pingpong_kernel(Bf16Args p)
     // to the register-staged loader (2-byte loads).  The vote goes through the dynamic
     // LDS: all 160 KiB are claimed by the slots, so nothing here may use static LDS.
     bool direct = true;
-    if (p.A_off) {
+    if constexpr (HAS_OFF) {
         int bad = 0;
         for (int i = tid; i < (int)p.batch; i += 512)
             bad |= (((p.A_off[i] | p.B_off[i]) & 7) != 0);
@@ -384,12 +399,17 @@ bf16_pingpong_kernel(Bf16Args p)
     tile_coords(blockIdx.x, p.tiles_m, p.tiles_n, tm, tn);
     const bool edge = (w >> 2) ? ((int64_t)(tm + 1) * PP_BM > p.M)
                                : (B_LAY != LAY_PACKED && (int64_t)(tn + 1) * PP_BN > p.N);
-    if (direct) {
-        if (!edge) pp_body<A_KMAJ, B_LAY, true, false, KIND>(p);
-        else pp_body<A_KMAJ, B_LAY, true, true, KIND>(p);
+    if constexpr (!HAS_OFF) {
+        if (!edge) pp_body<A_KMAJ, B_LAY, true, false, KIND, false>(p);
+        else pp_body<A_KMAJ, B_LAY, true, true, KIND, false>(p);
     } else {
-        if (!edge) pp_body<A_KMAJ, B_LAY, false, false, KIND>(p);
-        else pp_body<A_KMAJ, B_LAY, false, true, KIND>(p);
+        if (direct) {
+            if (!edge) pp_body<A_KMAJ, B_LAY, true, false, KIND, true>(p);
+            else pp_body<A_KMAJ, B_LAY, true, true, KIND, true>(p);
+        } else {
+            if (!edge) pp_body<A_KMAJ, B_LAY, false, false, KIND, true>(p);
+            else pp_body<A_KMAJ, B_LAY, false, true, KIND, true>(p);
+        }
     }
 }
 
@@ -404,18 +424,21 @@ static hipError_t launch_pp(const Problem &p)
     const bool ak = p.transA == 0;
     const int lay = p.b_packed ? LAY_PACKED : (p.transB == 1 ? LAY_K : LAY_MN);
     void (*kern)(Bf16Args) = nullptr;
-#define BRG_PICK(KIND)                                                                \
-    if (ak && lay == LAY_K) kern = bf16_pingpong_kernel<true, LAY_K, KIND>;            \
-    else if (ak && lay == LAY_MN) kern = bf16_pingpong_kernel<true, LAY_MN, KIND>;     \
-    else if (ak) kern = bf16_pingpong_kernel<true, LAY_PACKED, KIND>;                  \
-    else if (lay == LAY_K) kern = bf16_pingpong_kernel<false, LAY_K, KIND>;            \
-    else if (lay == LAY_MN) kern = bf16_pingpong_kernel<false, LAY_MN, KIND>;          \
-    else kern = bf16_pingpong_kernel<false, LAY_PACKED, KIND>;
-    if (p.in_s8) kern = bf16_pingpong_kernel<true, LAY_K, KIND_S8>;
-    else if (p.in_f8) kern = p.f8_e5m2 ? bf16_pingpong_kernel<true, LAY_K, KIND_BF8> : bf16_pingpong_kernel<true, LAY_K, KIND_F8>;
+#define BRG_PICK2(KIND, OFF)                                                               \
+    if (ak && lay == LAY_K) kern = bf16_pingpong_kernel<true, LAY_K, KIND, OFF>;            \
+    else if (ak && lay == LAY_MN) kern = bf16_pingpong_kernel<true, LAY_MN, KIND, OFF>;     \
+    else if (ak) kern = bf16_pingpong_kernel<true, LAY_PACKED, KIND, OFF>;                  \
+    else if (lay == LAY_K) kern = bf16_pingpong_kernel<false, LAY_K, KIND, OFF>;            \
+    else if (lay == LAY_MN) kern = bf16_pingpong_kernel<false, LAY_MN, KIND, OFF>;          \
+    else kern = bf16_pingpong_kernel<false, LAY_PACKED, KIND, OFF>;
+#define BRG_PICK(KIND)                                                                    \
+    if (p.A_off) { BRG_PICK2(KIND, true) } else { BRG_PICK2(KIND, false) }
+    if (p.in_s8) kern = bf16_pingpong_kernel<true, LAY_K, KIND_S8, false>;
+    else if (p.in_f8) kern = p.f8_e5m2 ? bf16_pingpong_kernel<true, LAY_K, KIND_BF8, false> : bf16_pingpong_kernel<true, LAY_K, KIND_F8, false>;
     else if (p.in_f16) { BRG_PICK(KIND_F16) } else { BRG_PICK(KIND_BF16) }
+#undef BRG_PICK2
 #undef BRG_PICK
-    static thread_local const void *configured[16] = {nullptr};
+    static thread_local const void *configured[32] = {nullptr};
     bool done = false;
     for (const void *c : configured)
         done = done || c == (const void *)kern;

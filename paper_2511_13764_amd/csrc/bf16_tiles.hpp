@@ -158,6 +158,12 @@ struct TileOffsets {
         const uint64_t v = (uint64_t)off[i];
         lo = (uint32_t)v;
         hi = (uint32_t)(v >> 32);
+        // Make the load complete here, inside the rare refill path.  Otherwise the compiler, which
+        // must assume at the join that this load may still be pending, puts an s_waitcnt vmcnt(0) in
+        // front of every v_readlane of get() - and vmcnt also counts the global->LDS loads in
+        // flight, so every tile switch would drain the whole prefetch pipeline (measured: +0.3 us
+        // per 64-deep tile).  The empty statement uses and redefines both registers.
+        asm volatile("" : "+v"(lo), "+v"(hi));
         base = first;
     }
     __device__ __forceinline__ void init(const int64_t *offsets, int64_t batch, int first, int lane)
