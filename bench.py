@@ -32,7 +32,8 @@ HBM_TBS = 8.0
 # bench line reports null as soon as they have changed.
 HEADLINE_TRAFFIC = {"variant": "bf16_pingpong_256x256x64",
                     "bytes": (98468.6 * 2.0 + 32774.8 * 1.0) * 1024.0,
-                    "files": ["paper_2511_13764_amd/csrc/bf16_pingpong.hip", "paper_2511_13764_amd/csrc/bf16_tiles.hpp"],
+                    "files": ["paper_2511_13764_amd/csrc/bf16_pingpong.hpp", "paper_2511_13764_amd/csrc/bf16_pingpong.hip",
+                              "paper_2511_13764_amd/csrc/bf16_tiles.hpp"],
                     "sources": "648b63242477d988"}
 WARMUP_FLOOR_MS = 100.0  # continuous load before any timed region (clock management settles in ~30 ms)
 

@@ -134,9 +134,9 @@ int gemm_f16(int transA, int transB, int64_t M, int64_t N, int64_t K,
  * bias 7, 3 fraction bits; no infinities, NaN = S.1111.111, largest value 448);
  * products are exact; C is fp32 if c_is_f32 != 0, else bf16 (one rounding to
  * nearest-even on store).  Layout and alignment rules of the matrix-instruction
- * kernels as for gemm_s8 ("NT", K a multiple of 128, 16-byte aligned, leading
- * dimensions multiples of 16); anything else runs on the general kernel, which widens
- * to fp32 and adds in fp32.
+ * kernels as for gemm_s8 (any layout, K a multiple of 128, 16-byte aligned, leading
+ * dimensions multiples of 16, an m- or n-contiguous extent a multiple of 16); anything
+ * else runs on the general kernel, which widens to fp32 and adds in fp32.
  * Accuracy of the sums on the matrix-instruction kernels: the 128-deep FP8 instruction
  * adds its 128 products with reduced precision - each product is aligned to the largest
  * one it is added with and cut off 13 bits below that one's leading bit - and adds the
@@ -166,10 +166,11 @@ int gemm_bf8(int transA, int transB, int64_t M, int64_t N, int64_t K,
  * types; Section 5(c)):  C[M,N] = (accumulate ? C : 0) + A[M,K] x B[K,N].
  * A, B: device, signed 8-bit; C: device, int32; lda/ldb/ldc in elements.  Sums wrap
  * modulo 2^32 like any int32 arithmetic (|sum| < 2^31 needs K <= 131071 in the worst
- * case).  The matrix-instruction kernels take the "NT" layout (transA == 0,
- * transB == 1: both operands contiguous in k) with K a multiple of 128, 16-byte
- * aligned bases and leading dimensions that are multiples of 16; every other layout,
- * size or alignment runs on a plain integer kernel with identical results.
+ * case).  The matrix-instruction kernels take all four layouts, with K a multiple of
+ * 128, 16-byte aligned bases, leading dimensions that are multiples of 16, and - for an
+ * operand that is contiguous in m or n (transA == 1, transB == 0) - that extent a
+ * multiple of 16; every other size or alignment runs on a plain integer kernel with
+ * identical results.
  */
 int gemm_s8(int transA, int transB, int64_t M, int64_t N, int64_t K,
             const int8_t *A, int64_t lda, const int8_t *B, int64_t ldb,

@@ -31,8 +31,8 @@ template <int BM, int BN, bool A_KMAJ, int B_LAY, int KIND>
 __global__ void __launch_bounds__(256)
 bf16_mfma_kernel(Bf16Args p)
 {
-    typedef typename TileOf<BM, 4, A_KMAJ>::type ATile;
-    typedef typename TileOf<BN, 4, B_LAY>::type BTile;
+    typedef typename TileOf<BM, 4, A_KMAJ ? LAY_K : LAY_MN, KIND>::type ATile;
+    typedef typename TileOf<BN, 4, B_LAY, KIND>::type BTile;
     constexpr int WM = BM / 2, WN = BN / 2;         // wave tile
     constexpr int TM = WM / 32, TN = WN / 32;       // MFMA tiles per wave tile
     constexpr uint32_t A_BYTES = BM * BK * 2, B_BYTES = BN * BK * 2;
@@ -236,10 +236,12 @@ static hipError_t launch_tile(const Problem &p)
     else if (lay == LAY_K) kern = bf16_mfma_kernel<BM, BN, false, LAY_K, KIND>;                \
     else if (lay == LAY_MN) kern = bf16_mfma_kernel<BM, BN, false, LAY_MN, KIND>;              \
     else kern = bf16_mfma_kernel<BM, BN, false, LAY_PACKED, KIND>;
-    if (p.in_s8) kern = bf16_mfma_kernel<BM, BN, true, LAY_K, KIND_S8>;
-    else if (p.in_f16) { BRG_PICK(KIND_F16) } else { BRG_PICK(KIND_BF16) }
+    if (p.in_s8) {
+        if (ak) kern = lay == LAY_K ? bf16_mfma_kernel<BM, BN, true, LAY_K, KIND_S8> : bf16_mfma_kernel<BM, BN, true, LAY_MN, KIND_S8>;
+        else kern = lay == LAY_K ? bf16_mfma_kernel<BM, BN, false, LAY_K, KIND_S8> : bf16_mfma_kernel<BM, BN, false, LAY_MN, KIND_S8>;
+    } else if (p.in_f16) { BRG_PICK(KIND_F16) } else { BRG_PICK(KIND_BF16) }
 #undef BRG_PICK
-    static thread_local const void *configured[13] = {nullptr};
+    static thread_local const void *configured[16] = {nullptr};
     bool done = false;
     for (const void *c : configured)
         done = done || c == (const void *)kern;
@@ -260,8 +262,13 @@ hipError_t launch_bf16_128x128(const Problem &p) { return launch_tile<128, 128>(
 bool bf16_mfma_eligible(const Problem &p)
 {
     if (in_8bit(p)) {
-        // one-byte elements: both operands k-contiguous, whole 128-byte k-rows, 16-byte aligned rows
-        return p.transA == 0 && p.transB == 1 && p.batch == 1 && !p.A_off && !p.B_off && p.nmat == 1 &&
+        // one-byte elements: whole 128-deep k-blocks, 16-byte aligned rows, and whole 16-byte
+        // chunks along m / n where that is the contiguous direction
+        if (p.transA == 1 && (p.M & 15))
+            return false;
+        if (p.transB == 0 && (p.N & 15))
+            return false;
+        return !p.b_packed && p.batch == 1 && !p.A_off && !p.B_off && p.nmat == 1 &&
                p.K % 128 == 0 && !((uintptr_t)p.A & 15) && !((uintptr_t)p.B & 15) && !(p.lda & 15) &&
                !(p.ldb & 15) && p.lda < (1 << 23) && p.ldb < (1 << 23) && p.K / 128 < ((int64_t)1 << 31) &&
                p.M * p.N < ((int64_t)1 << 40);

@@ -44,8 +44,8 @@ bf16_stream_kernel(Bf16Args p)
 {
     constexpr int NW = StreamWaves<BM>::value;
     static_assert(A_KMAJ || BM == 128, "an m-contiguous A needs the 128-row tile");
-    typedef typename TileOf<BM, NW, A_KMAJ ? LAY_K : LAY_MN>::type ATile;
-    typedef typename TileOf<ST_BN, NW, B_LAY>::type BTile;
+    typedef typename TileOf<BM, NW, A_KMAJ ? LAY_K : LAY_MN, KIND>::type ATile;
+    typedef typename TileOf<ST_BN, NW, B_LAY, KIND>::type BTile;
     constexpr int WGM = BM == 128 ? 2 : 1, WGN = NW / WGM;    // wave grid
     constexpr int WM = BM / WGM, WN = ST_BN / WGN;
     constexpr int TM = WM / 16, TN = WN / 16;                 // 16x16 MFMA tiles per wave
@@ -288,8 +288,8 @@ bf16_stream128_kernel(Bf16Args p)
 {
     constexpr int BM = 128, NL = 4;              // NL: loader waves
     static_assert(!kind_is_f8(KIND), "the 128-deep FP8 instruction takes a whole k-block");
-    typedef typename TileOf<BM, NL, A_KMAJ ? LAY_K : LAY_MN>::type ATile;
-    typedef typename TileOf<ST_BN, NL, B_LAY>::type BTile;
+    typedef typename TileOf<BM, NL, A_KMAJ ? LAY_K : LAY_MN, KIND>::type ATile;
+    typedef typename TileOf<ST_BN, NL, B_LAY, KIND>::type BTile;
     constexpr int WM = 64, WN = 64, TM = WM / 16, TN = WN / 16;
     constexpr uint32_t A_BYTES = BM * BK * 2, B_BYTES = ST_BN * BK * 2;
     constexpr uint32_t STAGE = A_BYTES + B_BYTES;
@@ -480,42 +480,53 @@ hipError_t launch_stream(const Problem &p)
     const dim3 grid((unsigned)(a.tiles_m * a.tiles_n), (unsigned)p.split, (unsigned)p.nmat);
     void (*kern)(Bf16Args) = nullptr;
     size_t lds = (size_t)ST_STAGES * (BM + ST_BN) * BK * 2;
-    if constexpr (BM == 128) {
-        // Everything but FP8 takes the loader / multiplier form of the 128-row tile.
-#define BRG_PICK128(AK, KIND)                                                                 \
+    // One-byte operands come unpacked in all four layouts; 16-bit ones also with a packed B.
+#define BRG_ST_B(AK, KIND)                                                                    \
+    kern = p.transB == 1 ? bf16_stream_kernel<BM, AK, LAY_K, KIND> : bf16_stream_kernel<BM, AK, LAY_MN, KIND>;
+#define BRG_ST_B3(AK, KIND)                                                                   \
+    kern = p.b_packed ? bf16_stream_kernel<BM, AK, LAY_PACKED, KIND>                           \
+           : p.transB == 1 ? bf16_stream_kernel<BM, AK, LAY_K, KIND> : bf16_stream_kernel<BM, AK, LAY_MN, KIND>;
+#define BRG_S128_B(AK, KIND)                                                                  \
+    kern = p.transB == 1 ? bf16_stream128_kernel<AK, LAY_K, KIND> : bf16_stream128_kernel<AK, LAY_MN, KIND>;
+#define BRG_S128_B3(AK, KIND)                                                                 \
     kern = p.b_packed ? bf16_stream128_kernel<AK, LAY_PACKED, KIND>                            \
            : p.transB == 1 ? bf16_stream128_kernel<AK, LAY_K, KIND> : bf16_stream128_kernel<AK, LAY_MN, KIND>;
+    if constexpr (BM == 128) {
+        // Everything but FP8 takes the loader / multiplier form of the 128-row tile.
         if (p.in_f8) {
-            kern = p.f8_e5m2 ? bf16_stream_kernel<BM, true, LAY_K, KIND_BF8> : bf16_stream_kernel<BM, true, LAY_K, KIND_F8>;
+            if (p.transA == 0) {
+                if (p.f8_e5m2) { BRG_ST_B(true, KIND_BF8) } else { BRG_ST_B(true, KIND_F8) }
+            } else {
+                if (p.f8_e5m2) { BRG_ST_B(false, KIND_BF8) } else { BRG_ST_B(false, KIND_F8) }
+            }
         } else {
             lds = (size_t)S128_STAGES * (BM + ST_BN) * BK * 2;
-            if (p.in_s8) {
-                kern = bf16_stream128_kernel<true, LAY_K, KIND_S8>;
-            } else if (p.transA == 0) {
-                if (p.in_f16) { BRG_PICK128(true, KIND_F16) } else { BRG_PICK128(true, KIND_BF16) }
+            if (p.transA == 0) {
+                if (p.in_s8) { BRG_S128_B(true, KIND_S8) }
+                else if (p.in_f16) { BRG_S128_B3(true, KIND_F16) } else { BRG_S128_B3(true, KIND_BF16) }
             } else {
-                if (p.in_f16) { BRG_PICK128(false, KIND_F16) } else { BRG_PICK128(false, KIND_BF16) }
+                if (p.in_s8) { BRG_S128_B(false, KIND_S8) }
+                else if (p.in_f16) { BRG_S128_B3(false, KIND_F16) } else { BRG_S128_B3(false, KIND_BF16) }
             }
         }
-#undef BRG_PICK128
     } else {
-#define BRG_PICK(KIND)                                                                        \
-    kern = p.b_packed ? bf16_stream_kernel<BM, true, LAY_PACKED, KIND>                         \
-           : p.transB == 1 ? bf16_stream_kernel<BM, true, LAY_K, KIND> : bf16_stream_kernel<BM, true, LAY_MN, KIND>;
         if (p.transA != 0)
             return hipErrorInvalidValue;            // the 32- and 64-row tiles need a k-contiguous A
         if (p.in_s8) {
-            kern = bf16_stream_kernel<BM, true, LAY_K, KIND_S8>;
+            BRG_ST_B(true, KIND_S8)
         } else if (p.in_f8) {
-            kern = p.f8_e5m2 ? bf16_stream_kernel<BM, true, LAY_K, KIND_BF8> : bf16_stream_kernel<BM, true, LAY_K, KIND_F8>;
+            if (p.f8_e5m2) { BRG_ST_B(true, KIND_BF8) } else { BRG_ST_B(true, KIND_F8) }
         } else if (p.in_f16) {
-            BRG_PICK(KIND_F16)
+            BRG_ST_B3(true, KIND_F16)
         } else {
-            BRG_PICK(KIND_BF16)
+            BRG_ST_B3(true, KIND_BF16)
         }
-#undef BRG_PICK
     }
-    static thread_local const void *configured[24] = {nullptr};
+#undef BRG_ST_B
+#undef BRG_ST_B3
+#undef BRG_S128_B
+#undef BRG_S128_B3
+    static thread_local const void *configured[40] = {nullptr};
     bool done = false;
     for (const void *c : configured)
         done = done || c == (const void *)kern;

@@ -376,6 +376,103 @@ struct MNMajorTile {
 };
 
 // ---------------------------------------------------------------------------
+// The same for one-byte elements (int8, FP8): an operand whose contiguous direction
+// is m or n.  A k-block is 128 k-rows of COLS bytes (the kernels count k in 2-byte
+// units, so their 64-deep block is 128 one-byte k).  LDS image: k-row kr takes COLS
+// bytes; its 16-byte chunk c (16 consecutive m/n) sits at chunk position c ^ swz(kr).
+// ds_read_b64_tr_b8 works on blocks of 16 lanes: lane i of a block supplies the
+// address of 8 consecutive columns (8*(i%2)..) of k-row i/2 and receives, for column
+// i, the 8 k-values of those rows in k order.  The 16 k-values a lane needs per
+// matrix instruction (k = 64*s + 16*(lane/16) + 0..15 for the 16x16 forms: the same
+// bytes a k-contiguous operand's 16-byte read gives it) are two such reads.  A
+// half-wave thus reads one chunk column of 16 k-rows kr0 + 0..7 and kr0 + 16 + 0..7:
+// the swizzle gives those 16 rows 16 different 16-byte positions of a 256-byte bank
+// window (256-byte rows: three bits of kr and bit 4; 128-byte rows hold two k-rows
+// per window, so bits 1-2 of kr and bit 4).
+// ---------------------------------------------------------------------------
+typedef __attribute__((ext_vector_type(2))) int i32x2;
+
+template <int COLS, int NW>
+struct MNMajorTile8 {
+    static_assert(COLS == 256 || COLS == 128, "row of 256 or 128 one-byte elements");
+    static constexpr int kChunksPerRow = COLS / 16;
+    static constexpr int kRowBytes = COLS;
+    static constexpr int kRowsPerInstr = 1024 / COLS;               // k-rows one wave-load covers
+    static constexpr int kInstr = 2 * BK * COLS / 1024;
+    static constexpr int kPerWave = kInstr / NW;
+
+    __device__ static int swz(int kr)
+    {
+        return COLS == 256 ? ((kr & 7) | (((kr >> 4) & 1) << 3)) : (((kr >> 1) & 3) | (((kr >> 4) & 1) << 2));
+    }
+
+    // `ld` is the row pitch in 2-byte units (the host halves the leading dimensions of
+    // one-byte operands), offsets returned are bytes.
+    __device__ static uint32_t dst_byte(int w, int j) { return (uint32_t)(w * kPerWave + j) * 1024u; }
+    __device__ static uint32_t src_rel_bytes(int w, int j, int lane, int64_t col0, int64_t col_limit, int64_t ld)
+    {
+        const int idx = (w * kPerWave + j) * 64 + lane;
+        const int kr = idx / kChunksPerRow;
+        const int pc = idx % kChunksPerRow;
+        const int c = pc ^ swz(kr);
+        const int64_t rel = (col0 + 16 * c < col_limit) ? 16 * c : 0;
+        return (uint32_t)((int64_t)kr * ld * 2 + rel);
+    }
+
+    __device__ static int64_t origin(int64_t first, int64_t) { return first / 2; }
+    __device__ static int64_t kstep(int64_t ld) { return 2 * (int64_t)BK * ld; }
+    // Scalar-base form (256-byte rows only): wave-load g covers k-rows 4g + lane / 16.  The
+    // swizzle depends on g through its parity (bits 0-2 of the k-row) and through bit 2
+    // (bit 4 of the k-row), which moves the chunk by +-128 bytes:
+    // offset = lane_off_bytes(g & 1) + (delta_applies(g) ? lane_delta_bytes : 0).
+    __device__ static int64_t instr_offset_bytes(int g, int64_t ld) { return (int64_t)g * kRowsPerInstr * ld * 2; }
+    __device__ static uint32_t lane_off_bytes(int parity, int lane, int64_t ld)
+    {
+        static_assert(COLS == 256, "scalar-base addressing is written for 256-byte rows");
+        const int kr_in = lane / kChunksPerRow;
+        const int pc = lane % kChunksPerRow;
+        const int c = pc ^ ((4 * parity + kr_in) & 7);
+        return (uint32_t)((int64_t)kr_in * ld * 2 + 16 * c);
+    }
+    __device__ static int32_t lane_delta_bytes(int lane) { return ((lane % kChunksPerRow) & 8) ? -128 : 128; }
+    __device__ static bool delta_applies(int g) { return (g >> 2) & 1; }
+    __device__ static bool lane_valid(int g, int lane, int64_t col0, int64_t col_limit)
+    {
+        const int kr = kRowsPerInstr * g + lane / kChunksPerRow;
+        const int c = (lane % kChunksPerRow) ^ swz(kr);
+        return col0 + 16 * c < col_limit;
+    }
+
+    // 16 k-values from k-row kr0 on for the 16 columns from col on (col % 16 == 0), lane
+    // i of each 16-lane block receiving column col + i.
+    __device__ static bf16x8 read16(LDS_AS char *tile, int col, int kr0, int i)
+    {
+        const int c = col >> 4;
+        i32x2 v[2];
+#pragma unroll
+        for (int rd = 0; rd < 2; ++rd) {
+            const int kr = kr0 + 8 * rd + (i >> 1);
+            const uint32_t byte = (uint32_t)(kr * kRowBytes + ((c ^ swz(kr)) << 4) + 8 * (i & 1));
+            v[rd] = __builtin_amdgcn_ds_read_tr8_b64_v2i32((LDS_AS i32x2 *)(tile + byte));
+        }
+        const i32x4 r = __builtin_shufflevector(v[0], v[1], 0, 1, 2, 3);
+        return __builtin_bit_cast(bf16x8, r);
+    }
+    // Operand of the 32x32 int8 instruction for 32-column tile t and 32-deep k-slice ks:
+    // lane l holds column t*32 + l%32 and k = 32*ks + 16*(l/32) + 0..15.
+    __device__ static bf16x8 read_frag(LDS_AS char *tile, int col_base, int t, int ks, int lane)
+    {
+        const int b = lane >> 4;
+        return read16(tile, col_base + t * 32 + 16 * (b & 1), 32 * ks + 16 * (b >> 1), lane & 15);
+    }
+    // Operand of the 16x16 instructions for 16-column tile t and 64-deep k-step s.
+    __device__ static bf16x8 read_frag16(LDS_AS char *tile, int col_base, int t, int s, int lane)
+    {
+        return read16(tile, col_base + t * 16, 64 * s + 16 * (lane >> 4), lane & 15);
+    }
+};
+
+// ---------------------------------------------------------------------------
 // B operand packed ahead of time in groups of 8 consecutive k: the VNNI layout of
 // Section 2.2 / Figure 1 with a factor of 8, the 8 bf16 values one MFMA lane
 // consumes.  Element (k, n) sits at ((k / 8) * n_pitch + n) * 8 + k % 8; "ld" is
@@ -424,14 +521,18 @@ struct PackedTile {
 
 // Operand layouts as template arguments (a bool "k-major" converts to the first two).
 constexpr int LAY_MN = 0, LAY_K = 1, LAY_PACKED = 2;
-template <int EXTENT, int NW, int LAYOUT>
+// KIND selects the one-byte image for an m/n-contiguous operand; k-contiguous one-byte
+// operands use the 2-byte image as it is (two k per unit).
+template <int EXTENT, int NW, int LAYOUT, int KIND = KIND_BF16>
 struct TileOf;
-template <int EXTENT, int NW>
-struct TileOf<EXTENT, NW, LAY_K> { typedef KMajorTile<EXTENT, NW> type; };
-template <int EXTENT, int NW>
-struct TileOf<EXTENT, NW, LAY_MN> { typedef MNMajorTile<EXTENT, NW> type; };
-template <int EXTENT, int NW>
-struct TileOf<EXTENT, NW, LAY_PACKED> { typedef PackedTile<EXTENT, NW> type; };
+template <int EXTENT, int NW, int KIND>
+struct TileOf<EXTENT, NW, LAY_K, KIND> { typedef KMajorTile<EXTENT, NW> type; };
+template <int EXTENT, int NW, int KIND>
+struct TileOf<EXTENT, NW, LAY_MN, KIND> {
+    typedef std::conditional_t<kind_is_8bit(KIND), MNMajorTile8<EXTENT, NW>, MNMajorTile<EXTENT, NW>> type;
+};
+template <int EXTENT, int NW, int KIND>
+struct TileOf<EXTENT, NW, LAY_PACKED, KIND> { typedef PackedTile<EXTENT, NW> type; };
 
 // XCD-aware tile order.  Workgroups are dealt round-robin to the 8 XCDs (each with
 // its own L2), so workgroup w is renumbered to t = (w % 8) * (T/8) + w / 8: every

@@ -161,6 +161,7 @@ inline bool in_16bit(const Problem &p) { return p.in_bf16 || p.in_f16; }
 // Operand kinds as template arguments of the kernels that move 128-byte k-rows.
 constexpr int KIND_BF16 = 0, KIND_F16 = 1, KIND_S8 = 2, KIND_F8 = 3, KIND_BF8 = 4;      // F8: E4M3, BF8: E5M2
 constexpr bool kind_is_f8(int kind) { return kind == KIND_F8 || kind == KIND_BF8; }
+constexpr bool kind_is_8bit(int kind) { return kind == KIND_S8 || kind_is_f8(kind); }
 inline bool in_8bit(const Problem &p) { return p.in_s8 || p.in_f8; }
 
 // ---- launchers (each returns the hipError_t of its launch) -------------------

@@ -78,8 +78,13 @@ def test_bf8_every_variant_nt(oracle):
             "bf16_stream_64x128x64", "bf16_stream_128x128x64"} <= ran
 
 
+@pytest.mark.parametrize("tA,tB", [(0, 0), (1, 0), (1, 1)])
+def test_bf8_every_variant_other_layouts(oracle, tA, tB):
+    F.every_variant_other_layout(run_bf8, oracle.f8e5m2_widen, lambda *a: ref_bf8(oracle, *a), bf8_bytes, 312, tA, tB, "bf8")
+
+
 @pytest.mark.parametrize("tA,tB", [(0, 0), (0, 1), (1, 0), (1, 1)])
-@pytest.mark.parametrize("M,N,K,pad", [(257, 131, 67, 3), (360, 520, 1024, 16), (16, 384, 2048, 0)])
+@pytest.mark.parametrize("M,N,K,pad", [(257, 131, 67, 3), (360, 520, 1024, 16), (16, 384, 2048, 0), (368, 528, 1024, 16)])
 def test_bf8_all_layouts_ragged_beta_bf16_out(oracle, M, N, K, pad, tA, tB):
     ra, ca = (K, M) if tA else (M, K)
     rb, cb = (N, K) if tB else (K, N)

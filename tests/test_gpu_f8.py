@@ -127,8 +127,75 @@ def test_f8_every_variant_nt(oracle):
     assert "bf16_128x128x64" not in ran
 
 
+F8_MFMA_VARIANTS = {"bf16_pingpong_256x256x64", "bf16_stream_32x128x64", "bf16_stream_64x128x64", "bf16_stream_128x128x64"}
+
+
+def every_variant_other_layout(run, widen, ref_fn, bytes_fn, seed, tA, tB, what):
+    """Shared by the two FP8 formats: operands contiguous in m / n (read out of LDS with the
+    transposing one-byte read) through every matrix-instruction kernel, fp32 out against the model
+    of the instruction, with and without a reduction split."""
+    M, N, K = 512, 768, 512
+    Al, Bt = bytes_fn(seed, 0, (M, K)), bytes_fn(seed, 1, (N, K))          # logical A and B^T
+    A = np.ascontiguousarray(Al.T) if tA else Al
+    Bm = Bt if tB else np.ascontiguousarray(Bt.T)
+    ref = ref_fn(A, Bm, M, N, K, tA, tB)
+    Aw, Bw = widen(Al).astype(np.float64), widen(Bt).astype(np.float64)
+    ws = B.gemm_workspace_bytes(1, M, N, K)
+    ran = set()
+    for v, name in enumerate(B.variants()):
+        for split in (1, 2):
+            say(f"{what} t{tA}{tB} variant={name} split={split}")
+            try:
+                out = run(A, Bm, M, N, K, tA, tB, workspace_bytes=ws, force=(v, split))
+            except B.BrgemmError as e:
+                assert e.code == B.INVALID_ARG
+                continue
+            ran.add(name)
+            if name.startswith("generic"):
+                assert H.rel_fro(out, ref) <= 1e-6, (name, split)
+            else:
+                check_f8_against_model(out[::4], ref[::4], Aw[::4], Bw, f"{what} t{tA}{tB} {name} split={split}")
+    expect = set(F8_MFMA_VARIANTS) if tA == 0 else {"bf16_pingpong_256x256x64", "bf16_stream_128x128x64"}
+    assert ran == expect | {"generic_64x64x16_f32mfma"}
+
+
+@pytest.mark.parametrize("tA,tB", [(0, 0), (1, 0), (1, 1)])
+def test_f8_every_variant_other_layouts(oracle, tA, tB):
+    every_variant_other_layout(run_f8, oracle.f8e4m3_widen, lambda *a: ref_f8(oracle, *a), f8_bytes, 303, tA, tB, "f8")
+
+
+@pytest.mark.parametrize("tA,tB", [(0, 0), (1, 0), (1, 1)])
+@pytest.mark.parametrize("name", ["bf16_pingpong_256x256x64", "bf16_stream_128x128x64"])
+def test_f8_edge_tiles_other_layouts(oracle, name, tA, tB):
+    """Tiles that overhang the matrix by whole 16-byte chunks in the contiguous direction; NaN bytes in
+    the row padding; integer-valued operands, so the result is exact."""
+    M, N, K = 256 + 112, 512 + 16, 1024
+    codes = np.array([0x00, 0x38, 0xB8, 0x40, 0xC0, 0x44, 0xC4, 0x48, 0xC8], np.uint8)    # 0, +-1, +-2, +-3, +-4
+    rng = np.random.default_rng(9 + 2 * tA + tB)
+    ra, ca = (K, M) if tA else (M, K)
+    rb, cb = (N, K) if tB else (K, N)
+    A = np.full((ra, ca + 16), 0x7F, np.uint8)
+    Bm = np.full((rb, cb + 16), 0x7F, np.uint8)
+    A[:, :ca] = rng.choice(codes, (ra, ca))
+    Bm[:, :cb] = rng.choice(codes, (rb, cb))
+    ref = ref_f8(oracle, A, Bm, M, N, K, tA, tB)
+    out = run_f8(A, Bm, M, N, K, tA, tB, force=(B.variants().index(name), 1))
+    assert (out == ref).all()
+
+
+def test_f8_nn_full_size_takes_the_pingpong_kernel(oracle):
+    M = N = K = 4096
+    A, Bm = f8_bytes(304, 0, (M, K)), f8_bytes(304, 1, (K, N), scale=0.05)
+    rows = H.sample_rows(M, 16)
+    ref = ref_f8(oracle, A, Bm, M, N, K, 0, 0, rows=rows)
+    out = run_f8(A, Bm, M, N, K, 0, 0)
+    assert B.gemm_variant_name(B.gemm_last_variant()) == "bf16_pingpong_256x256x64"
+    assert H.rel_fro(out[rows], ref) <= 1e-4
+
+
 @pytest.mark.parametrize("tA,tB", [(0, 0), (0, 1), (1, 0), (1, 1)])
-@pytest.mark.parametrize("M,N,K,pad", [(257, 131, 67, 3), (360, 520, 1024, 16), (16, 384, 2048, 0), (128, 256, 128, 0)])
+@pytest.mark.parametrize("M,N,K,pad", [(257, 131, 67, 3), (360, 520, 1024, 16), (16, 384, 2048, 0), (128, 256, 128, 0),
+                                       (368, 528, 1024, 16), (1040, 2064, 256, 0)])
 def test_f8_all_layouts_ragged_beta_bf16_out(oracle, M, N, K, pad, tA, tB):
     ra, ca = (K, M) if tA else (M, K)
     rb, cb = (N, K) if tB else (K, N)

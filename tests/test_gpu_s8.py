@@ -78,9 +78,56 @@ def test_s8_every_variant_nt(oracle):
         run_s8(A, Bm, M, N, K, 0, 1, force=(B.variants().index("bf16_128x128x64"), 2))
 
 
+MFMA_VARIANTS = {"bf16_128x128x64", "bf16_pingpong_256x256x64", "bf16_stream_32x128x64", "bf16_stream_64x128x64",
+                 "bf16_stream_128x128x64"}
+
+
+@pytest.mark.parametrize("tA,tB", [(0, 0), (1, 0), (1, 1)])
+def test_s8_every_variant_other_layouts(oracle, tA, tB):
+    """Operands contiguous in m / n (read out of LDS with the transposing one-byte read) through
+    every matrix-instruction kernel; the 32- and 64-row tiles need a k-contiguous A."""
+    M, N, K = 512, 768, 512
+    A, Bm = make(11 + 2 * tA + tB, M, N, K, tA, tB)
+    ref = as_i32(oracle.gemm_s8_ref(A, A.shape[1], Bm, Bm.shape[1], M, N, K, transA=tA, transB=tB))
+    ran = set()
+    for v, name in enumerate(B.variants()):
+        say(f"s8 t{tA}{tB} variant={name}")
+        try:
+            out = run_s8(A, Bm, M, N, K, tA, tB, force=(v, 1))
+        except B.BrgemmError as e:
+            assert e.code == B.INVALID_ARG
+            continue
+        ran.add(name)
+        assert (out == ref).all(), name
+    expect = set(MFMA_VARIANTS) if tA == 0 else MFMA_VARIANTS - {"bf16_stream_32x128x64", "bf16_stream_64x128x64"}
+    assert ran == expect | {"generic_64x64x16_f32mfma"}
+
+
+@pytest.mark.parametrize("tA,tB", [(0, 0), (1, 0), (1, 1)])
+@pytest.mark.parametrize("name", ["bf16_pingpong_256x256x64", "bf16_stream_128x128x64", "bf16_128x128x64"])
+def test_s8_edge_tiles_other_layouts(oracle, name, tA, tB):
+    """Tiles that overhang the matrix by whole 16-byte chunks in the contiguous direction, padded rows."""
+    M, N, K = 256 + 112, 512 + 16, 1024
+    A, Bm = make(21 + 2 * tA + tB, M, N, K, tA, tB, pad=16)
+    ref = as_i32(oracle.gemm_s8_ref(A, A.shape[1], Bm, Bm.shape[1], M, N, K, transA=tA, transB=tB))
+    out = run_s8(A, Bm, M, N, K, tA, tB, force=(B.variants().index(name), 1))
+    assert (out == ref).all()
+
+
+def test_s8_nn_full_size_takes_the_pingpong_kernel(oracle):
+    M = N = K = 4096
+    A, Bm = make(7, M, N, K, 0, 0)
+    rng = np.random.default_rng(8)
+    rows = sorted(set([0, 1, 15, 16, 127, 128, 255, 256, M - 1] + rng.integers(0, M, 12).tolist()))
+    out = run_s8(A, Bm, M, N, K, 0, 0)
+    assert B.gemm_variant_name(B.gemm_last_variant()) == "bf16_pingpong_256x256x64"
+    ref = oracle.gemm_s8_ref(np.ascontiguousarray(A[rows]), K, Bm, N, len(rows), N, K)
+    assert (out[rows] == as_i32(ref)).all()
+
+
 @pytest.mark.parametrize("tA,tB", [(0, 0), (0, 1), (1, 0), (1, 1)])
 @pytest.mark.parametrize("M,N,K,pad", [(257, 131, 67, 3), (1, 1, 1, 0), (360, 520, 1024, 16), (16, 384, 2048, 0),
-                                       (100, 72, 128, 5), (128, 256, 0, 0)])
+                                       (100, 72, 128, 5), (128, 256, 0, 0), (368, 528, 1024, 16), (1040, 2064, 256, 0)])
 def test_s8_all_layouts_ragged_accumulate(oracle, M, N, K, pad, tA, tB):
     A, Bm = make(2 + M + K, M, N, K, tA, tB, pad=pad)
     if K == 0:
