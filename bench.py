@@ -296,6 +296,10 @@ def main():
                lambda: B.gemm_s8(0, 1, 4096, 4096, 4096, a, 4096, b, 4096, 0, c, 4096), 5033.2, steps=100)
         others["s8_4096_nt"]["unit"] = "TOP/s (tflops / frac_mfma_peak fields), against 5033.2 TOP/s int8 MFMA"
         others["s8_4096_nt"]["frac_of_measured_mfma_rate"] = round(others["s8_4096_nt"]["tflops"] / measured["s8_uniform_operands"], 4)
+        # the same with B stored K x N (n-contiguous: re-laid-out by the transposing one-byte LDS read)
+        record("s8_4096_nn", 2.0 * 4096 ** 3,
+               lambda: B.gemm_s8(0, 0, 4096, 4096, 4096, a, 4096, b, 4096, 0, c, 4096), 5033.2, steps=100)
+        others["s8_4096_nn"]["unit"] = others["s8_4096_nt"]["unit"]
         del a, b, c
         # FP8 (E4M3) operands, bf16 results (NT); peak 5.0 PFLOP/s dense fp8
         a = torch.randn((4096, 4096), device="cuda").to(torch.float8_e4m3fn)
@@ -305,6 +309,9 @@ def main():
                lambda: B.gemm_f8(0, 1, 4096, 4096, 4096, a, 4096, b, 4096, 0.0, c, 4096, 0, workspace=ws), 5033.2,
                steps=100)
         others["f8_4096_nt"]["frac_of_measured_mfma_rate"] = round(others["f8_4096_nt"]["tflops"] / measured["f8_normal_operands"], 4)
+        record("f8_4096_nn", 2.0 * 4096 ** 3,
+               lambda: B.gemm_f8(0, 0, 4096, 4096, 4096, a, 4096, b, 4096, 0.0, c, 4096, 0, workspace=ws), 5033.2,
+               steps=100)
         del a, b, c
         # MLP shapes, weights stored N x K
         # The skinny cases are bound by the stream of the 90 MB weight matrix, which fits
