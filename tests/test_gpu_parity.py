@@ -336,6 +336,49 @@ def test_brgemm_small_scattered(oracle, tA, tB, M, N, K, batch):
     assert np.array_equal(out_s, out_s2), "split reduction must be deterministic"
 
 
+@pytest.mark.parametrize("tA,tB", [(0, 0), (0, 1), (1, 0)])
+@pytest.mark.parametrize("odd_tile", [None, 3, 140])
+def test_brgemm_more_than_64_tiles_every_variant(oracle, tA, tB, odd_tile):
+    """The kernels keep 64 tile offsets at a time in registers: 150 tiles of one k-block each make
+    every wave refill that window twice (more often under a split), through every variant.
+    odd_tile: one tile starts at an odd element (inside or beyond the first window), which must
+    send the kernels to their register-staged loads with identical results."""
+    M, N, K, batch = 256, 384, 64, 150
+    rng = np.random.default_rng(77 + 2 * tA + tB)
+    lda, ldb = (M if tA else K), (K if tB else N)
+    a_sz, b_sz = (K if tA else M) * lda, (N if tB else K) * ldb
+    slot = max(a_sz, b_sz) + 64
+    pool = np.full(slot * 2 * batch + 64, W.BF16_NAN, np.uint16)
+    order = rng.permutation(2 * batch)
+    A_off = order[:batch].astype(np.int64) * slot + 8 * rng.integers(0, 4, batch)
+    B_off = order[batch:].astype(np.int64) * slot + 8 * rng.integers(0, 4, batch)
+    if odd_tile is not None:
+        A_off[odd_tile] += 3
+    for i in range(batch):
+        pool[A_off[i]:A_off[i] + a_sz] = W.normal_bf16(67, i, (a_sz,))
+        pool[B_off[i]:B_off[i] + b_sz] = W.normal_bf16(67, 1000 + i, (b_sz,))
+    case = W.BrgemmCase(f"brgemm_150tiles_t{tA}{tB}_odd{odd_tile}", M, N, K, batch, tA, tB, 0.0,
+                        pool, A_off, B_off, lda, ldb, None)
+    ref = H.oracle_brgemm_case(oracle, case)
+    ws = B.gemm_workspace_bytes(1, M, N, K, batch)
+    ran = set()
+    for v, name in enumerate(B.variants()):
+        for split in (1, 2, 7):
+            say(f"{case.name} variant={name} split={split}")
+            try:
+                out = H.run_brgemm_case(case, workspace_bytes=ws, force=(v, split))
+            except B.BrgemmError as e:
+                assert e.code == B.INVALID_ARG
+                continue
+            ran.add(name)
+            assert np.isfinite(out).all(), (name, split)
+            assert H.rel_fro(out, ref) <= H.TOL_BF16_F32OUT, (name, split)
+    want = {"generic_64x64x16_f32mfma", "bf16_128x128x64", "bf16_pingpong_256x256x64", "bf16_stream_128x128x64"}
+    if tA == 0:
+        want |= {"bf16_stream_32x128x64", "bf16_stream_64x128x64"}
+    assert want <= ran, ran
+
+
 @pytest.mark.parametrize("tA,tB", [(0, 0), (0, 1), (1, 0), (1, 1)])
 @pytest.mark.parametrize("M,N,K,batch", [(128, 256, 64, 9), (32, 384, 128, 5), (256, 512, 128, 3)])
 def test_brgemm_tile_offsets_not_16_byte_aligned(oracle, tA, tB, M, N, K, batch):
