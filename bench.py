@@ -378,7 +378,34 @@ def main():
         record("brgemm_512x512x64x64", c5.flops,
                lambda: B.brgemm_bf16(0, 0, c5.M, c5.N, c5.K, c5.batch, pool, ao, c5.lda, pool, bo, c5.ldb, 1.0,
                                      cc, c5.N, workspace=ws), PEAK_BF16, steps=200, warmup=20)
+        del pool, ao, bo, cc
+        # Context only, not a path of this library: the vendor GEMM library as PyTorch calls it
+        # (torch.matmul), same box, same clock state, same shapes and value distributions.
+        vendor = {}
+
+        def vendor_time(name, flops_, fn):
+            settle(fn)
+            _, e_ = time_launches(fn, 50, 20)
+            vendor[name] = {"us": round(e_ * 1e6, 2), "tflops": round(flops_ / e_ / 1e12, 2)}
+
+        for s_ in (2048, 4096):
+            a = torch.randn((s_, s_), device="cuda").to(torch.bfloat16)
+            b = torch.randn((s_, s_), device="cuda").to(torch.bfloat16)
+            c = torch.empty((s_, s_), device="cuda", dtype=torch.bfloat16)
+            vendor_time(f"bf16_{s_}", 2.0 * s_ ** 3, lambda: torch.matmul(a, b, out=c))
+            del a, b, c
+        a = torch.randn((4096, 4096), device="cuda").to(torch.bfloat16)
+        w = (torch.randn((11008, 4096), device="cuda") * 0.02).to(torch.bfloat16)
+        c = torch.empty((4096, 11008), device="cuda", dtype=torch.bfloat16)
+        vendor_time("mlp_up_M4096", 2.0 * 4096 * 11008 * 4096, lambda: torch.matmul(a, w.t(), out=c))
+        del a, w, c
+        a = torch.rand((2048, 2048), device="cuda") * 2 - 1
+        b = torch.rand((2048, 2048), device="cuda") * 2 - 1
+        c = torch.empty((2048, 2048), device="cuda")
+        vendor_time("f32_2048", 2.0 * 2048 ** 3, lambda: torch.matmul(a, b, out=c))
+        del a, b, c
         out["others"] = others
+        out["vendor_library_via_torch_matmul"] = vendor
 
     print(json.dumps(out))
 
