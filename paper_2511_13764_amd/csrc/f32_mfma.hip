@@ -176,22 +176,29 @@ f32_mfma_kernel(F32Args p)
     };
     // The same reads one at a time (unit u: the A tiles first, then the B tiles), so
     // that they can be placed between individual MFMAs.
-    constexpr int UA = A_KMAJ ? 2 : 8, UB = B_KMAJ ? TN : 4 * TN, UNITS = UA + UB;
+    // (An m/n-contiguous operand is read two consecutive k at a time: the two 32-bit reads sit
+    // 512 bytes apart and become one ds_read2st64_b32, which halves the LDS instructions of that
+    // operand - they, not the bytes, are what the matrix pipe loses time to.)
+    constexpr int UA = A_KMAJ ? 2 : 4, UB = B_KMAJ ? TN : 2 * TN, UNITS = UA + UB;
     auto read_unit = [&](int stage, int j, int buf, auto uc) {
         constexpr int u = decltype(uc)::value;
         LDS_AS char *at = smem + (uint32_t)stage * F_STAGE;
         LDS_AS char *bt = at + F_OP_BYTES;
         if constexpr (u < UA) {
-            if constexpr (A_KMAJ)
+            if constexpr (A_KMAJ) {
                 fa[buf][u] = *(LDS_AS f32x4 *)(at + FKTile::frag_byte(wm * 64, u, j, lane));
-            else
-                fa[buf][u / 4][u % 4] = FMNTile::read(at, wm * 64, u / 4, j, u % 4, lane);
+            } else {
+                fa[buf][u / 2][2 * (u % 2)] = FMNTile::read(at, wm * 64, u / 2, j, 2 * (u % 2), lane);
+                fa[buf][u / 2][2 * (u % 2) + 1] = FMNTile::read(at, wm * 64, u / 2, j, 2 * (u % 2) + 1, lane);
+            }
         } else {
             constexpr int v = u - UA;
-            if constexpr (B_KMAJ)
+            if constexpr (B_KMAJ) {
                 fb[buf][v] = *(LDS_AS f32x4 *)(bt + FKTile::frag_byte(wn * WN, v, j, lane));
-            else
-                fb[buf][v / 4][v % 4] = FMNTile::read(bt, wn * WN, v / 4, j, v % 4, lane);
+            } else {
+                fb[buf][v / 2][2 * (v % 2)] = FMNTile::read(bt, wn * WN, v / 2, j, 2 * (v % 2), lane);
+                fb[buf][v / 2][2 * (v % 2) + 1] = FMNTile::read(bt, wn * WN, v / 2, j, 2 * (v % 2) + 1, lane);
+            }
         }
     };
     // One j-step: 8 * TN MFMAs with this wave's other work threaded between them.  An
